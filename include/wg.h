@@ -1,0 +1,181 @@
+/*
+ * wg.h -- C ABI of the MI355X structured-decoding hot path.
+ *
+ * The library implements the per-output-token work of operator-based structured
+ * decoding (Sequence / Write / Wait / IfElse / DoWhile operators tracked by a
+ * finite-state machine, masks built from each operator's allow / wait sets and
+ * cached globally): for every request of a decode batch it produces the
+ * vocabulary mask of the request's current state, sets the logits of disallowed
+ * tokens to -inf, and advances the state on the sampled token.  All per-step
+ * work runs in HIP kernels on gfx950; there is no CPU fallback.
+ *
+ * Conventions
+ *   - Symbols are bytes 0..255 plus end-of-sequence.  A vocabulary token is a
+ *     byte string; the token `eos_id` is the one-symbol string [EOS].  A token
+ *     is allowed in a state iff feeding its bytes one at a time never meets an
+ *     undefined transition.
+ *   - A request's state is (sid, aux): sid is the leaf state (0 = FINAL,
+ *     0xFFFFFFFF = ERROR), aux the number of allow-bytes consumed so far inside
+ *     a bounded Wait (0 elsewhere).
+ *   - Leaf states are numbered per template in pre-order (Sequence children in
+ *     order; a Wait, then its body; IfElse: condition, if_body, else_body;
+ *     DoWhile: body, then condition), one id per Write byte, then one END id.
+ *     Template 0 starts at id 1, template k where k-1 ended.
+ *   - Masks are [B][W] uint32, W = ceil(V/32); token t is bit (t & 31) of word
+ *     t >> 5; bits at and above V are zero.
+ *   - "device" pointers are HIP device memory owned by the caller, "host"
+ *     pointers are ordinary memory.  `stream` is a hipStream_t passed as
+ *     void* (NULL = the default stream).
+ *   - Every function returns WG_OK (0) or a negative wg_status_t and never
+ *     throws or exits; wg_last_error() describes the last failure on the
+ *     calling thread.
+ *   - Calls that take a stream only enqueue work: they do not synchronise,
+ *     allocate or copy between host and device.  Calls on one handle must be
+ *     ordered on one stream (or otherwise serialised by the caller); the mask
+ *     cache of a handle is shared state.
+ */
+#ifndef WG_H
+#define WG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct wg_vocab_s  *wg_vocab_t;    /* device copy of the token-byte vocabulary */
+typedef struct wg_handle_s *wg_handle_t;   /* compiled templates + device mask cache */
+typedef struct wg_table_s  *wg_table_t;    /* host-only lowered state table (inspection) */
+
+typedef struct { uint32_t sid; uint32_t aux; } wg_state_t;
+
+#define WG_SID_FINAL 0u
+#define WG_SID_ERROR 0xFFFFFFFFu
+#define WG_UNBOUNDED 0xFFFFFFFFu
+
+typedef enum { WG_F32 = 0, WG_BF16 = 1 } wg_dtype_t;
+
+/* What an accepted end-of-sequence does: stop in FINAL (which then only accepts
+ * further EOS), or re-arm the request at its template's start state (continuous
+ * batching: the slot is reused by the next request of the same shape). */
+enum { WG_EOS_STOP = 0u, WG_EOS_RESTART = 1u };
+
+typedef enum {
+    WG_OK = 0,
+    WG_ERR_INVALID = -1,    /* null pointer, zero size, bad enum, size mismatch */
+    WG_ERR_PARSE = -2,      /* malformed template or argument binding */
+    WG_ERR_NOMEM = -3,      /* host or device allocation failed / cache would not fit */
+    WG_ERR_HIP = -4         /* a HIP runtime call failed */
+} wg_status_t;
+
+/* Runtime snippet arguments of one template instance: names[i] binds $names[i]
+ * to the bytes data[i][0 .. lens[i]).  In Write($x) the bytes are the literal;
+ * in a set position (allow=$x, wait={a, $x}) they are the set of those bytes. */
+typedef struct {
+    uint32_t n;
+    const char *const *names;
+    const uint8_t *const *data;
+    const uint64_t *lens;
+} wg_args_t;
+
+typedef struct {
+    uint64_t lookups;       /* request-steps served by wg_fill_masks */
+    uint64_t hits;          /* ... whose mask was already cached */
+    uint64_t builds;        /* mask rows built (one per distinct missing key) */
+    uint64_t keys;          /* cache keys the handle can hold (fixed at compile) */
+    uint64_t arena_bytes;   /* device bytes reserved for cached rows */
+} wg_cache_stats_t;
+
+/* State kinds reported by wg_table_state. */
+enum { WG_KIND_FINAL = 0, WG_KIND_LIT = 1, WG_KIND_WAIT = 2, WG_KIND_COND = 3, WG_KIND_END = 4 };
+
+typedef struct {
+    uint32_t kind;          /* WG_KIND_* */
+    uint32_t byte;          /* LIT: the expected byte */
+    uint32_t next_a;        /* LIT / WAIT: successor; COND: target of true_waits */
+    uint32_t next_b;        /* COND: target of false_waits */
+    uint32_t eos_next;      /* state after EOS, or WG_SID_ERROR if EOS is rejected */
+    uint32_t max;           /* WAIT: bound on consumed allow-bytes, or WG_UNBOUNDED */
+    uint32_t tmpl;          /* template instance the state belongs to */
+    uint32_t n_keys;        /* distinct masks this state can have (budget variants) */
+} wg_state_info_t;
+
+/* ---- vocabulary ---------------------------------------------------------------------
+ * CSR token bytes: token t is host_bytes[host_offsets[t] .. host_offsets[t+1]).  Both
+ * arrays are host memory and are copied; eos_id < 0 means "no EOS token".  A token
+ * with no bytes other than eos_id is never allowed.  The vocabulary is uploaded to
+ * HBM once and may be shared by several handles; destroy it after them. */
+int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uint32_t V,
+                    int32_t eos_id, wg_vocab_t *out);
+void wg_vocab_destroy(wg_vocab_t v);
+
+/* ---- compilation (the paper's split into a static structure precompiled once and
+ * dynamic arguments instantiated per request; section "Collaborative Parsing") ---------
+ * templates[i] is UTF-8 text in the operator syntax of the paper's listing in the
+ * section "Operator Building and State Tracking":
+ *     Sequence(op, ...)            Write("bytes") | Write($arg)
+ *     Wait(allow={..} | denies={..}, wait={..} [, max=N] [, body=op])
+ *     Wait(allow={..}, true_waits={..}, false_waits={..})        (condition)
+ *     IfElse(condition=Wait(..), if_body=op|None, else_body=op|None)
+ *     DoWhile(body=op|None, condition=Wait(..))
+ * Set elements: a byte, \d \w \s, \xHH, \n \t \r, \c (the byte c), [a-z0-9] classes,
+ * <eos>, $arg.  Identical template texts are parsed once and instantiated per args[i]
+ * (args may be NULL when no template has holes).  start_states_out[i] (host, may be
+ * NULL) receives the start state of instance i.  The resulting handle serves a
+ * heterogeneous batch: state ids are global to the handle.
+ * wg_lower does the host part only (no GPU needed) and returns an inspectable table;
+ * lmax is the longest token length the masks will be built for. */
+int wg_lower(const char *const *templates, const wg_args_t *args, uint32_t n_templates,
+             uint32_t flags, uint32_t lmax, wg_table_t *out);
+uint32_t wg_table_num_states(wg_table_t t);
+uint32_t wg_table_start_state(wg_table_t t, uint32_t instance);
+int wg_table_state(wg_table_t t, uint32_t sid, wg_state_info_t *out);
+/* class of a byte in state sid: 0 reject, 1 stay, 2 exit to next_a, 3 exit to next_b;
+ * for symbol 256 (EOS): 2 if accepted (the state after it is eos_next), else 0 */
+int wg_table_symbol_class(wg_table_t t, uint32_t sid, uint32_t symbol);
+void wg_table_destroy(wg_table_t t);
+
+int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_templates,
+               wg_vocab_t vocab, uint32_t flags, wg_handle_t *out, wg_state_t *start_states_out);
+void wg_destroy(wg_handle_t h);
+uint32_t wg_num_states(wg_handle_t h);
+uint32_t wg_mask_words(wg_handle_t h);      /* W = ceil(V/32) */
+
+/* ---- per-step calls (device pointers, enqueue only) -------------------------------------
+ * wg_fill_masks: d_bitmask[b][0..W) <- mask of d_states[b] (mask creation with the global
+ * cache of the section "Mask Generation and Global Caching"): cached rows are gathered,
+ * missing ones are built once per distinct key and cached.  An ERROR or out-of-range
+ * state gets an all-zero row. */
+int wg_fill_masks(wg_handle_t h, const wg_state_t *d_states, uint32_t B, uint32_t *d_bitmask,
+                  void *stream);
+
+/* wg_apply_mask: in place, logits[b][t] <- -inf (0xFF800000 / 0xFF80) where the mask bit is
+ * 0; other elements keep their bit pattern.  Row b starts row_stride_elems * b elements
+ * after d_logits (row_stride_elems >= V); the mask row stride is ceil(V/32) words. */
+int wg_apply_mask(void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V,
+                  int64_t row_stride_elems, const uint32_t *d_bitmask, void *stream);
+
+/* wg_advance: d_states[b] <- state after d_tokens[b] (state tracking, constant work per
+ * symbol).  A token the state rejects, or a token id outside [0, V), gives
+ * {WG_SID_ERROR, 0} and increments the handle's device error counter. */
+int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B,
+               void *stream);
+
+/* Forget every cached mask (O(1): bumps the cache epoch on the device). */
+int wg_cache_clear(wg_handle_t h, void *stream);
+
+/* ---- introspection (these synchronise the device) ---------------------------------------- */
+int wg_cache_stats(wg_handle_t h, wg_cache_stats_t *host_out);
+int wg_error_count(wg_handle_t h, uint64_t *host_out);
+const char *wg_last_error(void);
+
+/* ---- sampler stand-in for harnesses (not part of the decoding path) ----------------------
+ * d_tokens[b] <- index of the (d_draws[b] mod popcount)-th set bit of mask row b, or -1 for
+ * an all-zero row. */
+int wg_select_tokens(const uint32_t *d_bitmask, uint32_t B, uint32_t V, const uint64_t *d_draws,
+                     int32_t *d_tokens, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WG_H */

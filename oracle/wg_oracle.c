@@ -289,6 +289,7 @@ static Node *parse_body(Parser *p)                    /* an operator or None */
 {
     int none = 0;
     Node *n = parse_op(p, &none);
+    if (n && n->kind == N_COND) { fail(p, "a condition Wait is only valid inside IfElse / DoWhile"); return NULL; }
     return none ? NULL : n;
 }
 
@@ -382,6 +383,7 @@ static Node *parse_op(Parser *p, int *is_none)
             if (c == ',') { p->i++; continue; }
             Node *k = parse_op(p, NULL);
             if (p->failed) return NULL;
+            if (k->kind == N_COND) { fail(p, "a condition Wait is only valid inside IfElse / DoWhile"); return NULL; }
             if (n->nkids == cap) {
                 cap = cap ? 2 * cap : 8;
                 Node **nk = (Node **)palloc(p, (size_t)cap * sizeof(Node *));
@@ -552,6 +554,7 @@ wgo_handle *wgo_compile(const char *const *texts, const wgo_args *args, uint32_t
         p->err = msg; p->errlen = sizeof msg;
         roots[t] = parse_op(p, NULL);
         if (!p->failed && peek(p) >= 0) fail(p, "trailing text after the operator");
+        if (!p->failed && roots[t]->kind == N_COND) fail(p, "a condition Wait is only valid inside IfElse / DoWhile");
         if (p->failed) { seterr(err, errlen, msg, t); ok = 0; break; }
         number(roots[t], &next_id);
         h->end[t] = next_id++;

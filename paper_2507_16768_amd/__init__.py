@@ -1,0 +1,9 @@
+"""MI355X-native hot path of operator-based structured decoding (mask creation with a
+device-resident cache, logit masking, state advance) behind a small C ABI.
+
+`binding` wraps the shared library one-to-one; it marshals arguments and nothing else.
+"""
+from .binding import (  # noqa: F401
+    WgError, Vocab, Handle, Table, apply_mask, select_tokens, load_library, library_path,
+    F32, BF16, EOS_STOP, EOS_RESTART, SID_FINAL, SID_ERROR,
+)

@@ -1,0 +1,270 @@
+"""ctypes binding of libwgrammar.so: same names as the C ABI, argument marshalling only.
+
+Device buffers are torch tensors (torch is used for device memory and streams, nothing
+else).  There is no fallback: if the shared library is missing, loading fails.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+# torch is imported before the shared library is opened on purpose: the process must hold
+# exactly one HIP runtime, and it has to be the one torch's device tensors and streams
+# belong to.  libwgrammar.so then binds to that already-loaded runtime by its soname.
+import torch  # noqa: F401
+
+from . import build as _build
+
+F32, BF16 = 0, 1
+EOS_STOP, EOS_RESTART = 0, 1
+SID_FINAL, SID_ERROR = 0, 0xFFFFFFFF
+
+_lib = None
+
+
+class WgError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("wg status %d: %s" % (code, msg))
+        self.code = code
+
+
+class _Args(C.Structure):
+    _fields_ = [("n", C.c_uint32), ("names", C.POINTER(C.c_char_p)),
+                ("data", C.POINTER(C.POINTER(C.c_uint8))), ("lens", C.POINTER(C.c_uint64))]
+
+
+class _Stats(C.Structure):
+    _fields_ = [(k, C.c_uint64) for k in ("lookups", "hits", "builds", "keys", "arena_bytes")]
+
+
+class _StateInfo(C.Structure):
+    _fields_ = [(k, C.c_uint32) for k in ("kind", "byte", "next_a", "next_b", "eos_next", "max",
+                                           "tmpl", "n_keys")]
+
+
+EXPORTS = [
+    "wg_vocab_create", "wg_vocab_destroy", "wg_lower", "wg_table_num_states",
+    "wg_table_start_state", "wg_table_state", "wg_table_symbol_class", "wg_table_destroy",
+    "wg_compile", "wg_destroy", "wg_num_states", "wg_mask_words", "wg_fill_masks",
+    "wg_apply_mask", "wg_advance", "wg_cache_clear", "wg_cache_stats", "wg_error_count",
+    "wg_last_error", "wg_select_tokens",
+]
+
+
+def library_path():
+    return _build.LIB
+
+
+def load_library():
+    """Loads the in-tree shared library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    path = library_path()
+    if not os.path.exists(path):
+        raise FileNotFoundError(
+            path + " is missing: build it first (python -m paper_2507_16768_amd.build)")
+    L = C.CDLL(path)
+    vp, u32, i32, u64, i64 = C.c_void_p, C.c_uint32, C.c_int32, C.c_uint64, C.c_int64
+    L.wg_last_error.restype = C.c_char_p
+    L.wg_vocab_create.argtypes = [vp, vp, u32, i32, C.POINTER(vp)]
+    L.wg_vocab_destroy.argtypes = [vp]
+    L.wg_vocab_destroy.restype = None
+    L.wg_lower.argtypes = [C.POINTER(C.c_char_p), C.POINTER(_Args), u32, u32, u32, C.POINTER(vp)]
+    L.wg_table_num_states.argtypes = [vp]
+    L.wg_table_num_states.restype = u32
+    L.wg_table_start_state.argtypes = [vp, u32]
+    L.wg_table_start_state.restype = u32
+    L.wg_table_state.argtypes = [vp, u32, C.POINTER(_StateInfo)]
+    L.wg_table_symbol_class.argtypes = [vp, u32, u32]
+    L.wg_table_destroy.argtypes = [vp]
+    L.wg_table_destroy.restype = None
+    L.wg_compile.argtypes = [C.POINTER(C.c_char_p), C.POINTER(_Args), u32, vp, u32, C.POINTER(vp), vp]
+    L.wg_destroy.argtypes = [vp]
+    L.wg_destroy.restype = None
+    L.wg_num_states.argtypes = [vp]
+    L.wg_num_states.restype = u32
+    L.wg_mask_words.argtypes = [vp]
+    L.wg_mask_words.restype = u32
+    L.wg_fill_masks.argtypes = [vp, vp, u32, vp, vp]
+    L.wg_apply_mask.argtypes = [vp, C.c_int, u32, u32, i64, vp, vp]
+    L.wg_advance.argtypes = [vp, vp, vp, u32, vp]
+    L.wg_cache_clear.argtypes = [vp, vp]
+    L.wg_cache_stats.argtypes = [vp, C.POINTER(_Stats)]
+    L.wg_error_count.argtypes = [vp, C.POINTER(u64)]
+    L.wg_select_tokens.argtypes = [vp, u32, u32, vp, vp, vp]
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc != 0:
+        raise WgError(rc, load_library().wg_last_error().decode(errors="replace"))
+
+
+def _marshal_templates(texts, args):
+    n = len(texts)
+    enc = [t.encode("utf-8") if isinstance(t, str) else bytes(t) for t in texts]
+    c_texts = (C.c_char_p * max(n, 1))(*enc)
+    keep = [enc, c_texts]
+    c_args = None
+    if args is not None:
+        if len(args) != n:
+            raise ValueError("one argument set per template is required")
+        c_args = (_Args * max(n, 1))()
+        for i, a in enumerate(args):
+            names = [k.encode() for k in a]
+            vals = [np.frombuffer(bytes(v), dtype=np.uint8).copy() for v in a.values()]
+            m = len(names)
+            c_names = (C.c_char_p * max(m, 1))(*names)
+            c_data = (C.POINTER(C.c_uint8) * max(m, 1))(
+                *[v.ctypes.data_as(C.POINTER(C.c_uint8)) for v in vals])
+            c_lens = (C.c_uint64 * max(m, 1))(*[len(v) for v in vals])
+            c_args[i] = _Args(m, c_names, c_data, c_lens)
+            keep += [names, vals, c_names, c_data, c_lens]
+        keep.append(c_args)
+    return c_texts, c_args, n, keep
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    if hasattr(stream, "cuda_stream"):
+        return C.c_void_p(stream.cuda_stream)
+    return C.c_void_p(int(stream))
+
+
+def _dev(t, dtype=None, name="tensor"):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(name + " must be a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError("%s must have dtype %s" % (name, dtype))
+    return C.c_void_p(t.data_ptr())
+
+
+class Table:
+    """wg_lower: host-only lowering, for inspecting the state table without a GPU."""
+
+    def __init__(self, texts, args=None, flags=EOS_STOP, lmax=0):
+        L = load_library()
+        c_texts, c_args, n, _keep = _marshal_templates(texts, args)
+        self._t = C.c_void_p()
+        _check(L.wg_lower(c_texts, c_args, n, flags, lmax, C.byref(self._t)))
+        self.n_templates = n
+        self.num_states = L.wg_table_num_states(self._t)
+
+    def start_state(self, i=0):
+        return load_library().wg_table_start_state(self._t, i)
+
+    def state(self, sid):
+        info = _StateInfo()
+        _check(load_library().wg_table_state(self._t, sid, C.byref(info)))
+        return {k: getattr(info, k) for k, _ in _StateInfo._fields_}
+
+    def symbol_class(self, sid, symbol):
+        r = load_library().wg_table_symbol_class(self._t, sid, symbol)
+        if r < 0:
+            _check(r)
+        return r
+
+    def __del__(self):
+        if getattr(self, "_t", None):
+            load_library().wg_table_destroy(self._t)
+            self._t = None
+
+
+class Vocab:
+    """wg_vocab_create: uploads CSR token bytes to HBM."""
+
+    def __init__(self, token_bytes, offsets, eos_id):
+        L = load_library()
+        if isinstance(token_bytes, (bytes, bytearray)):
+            token_bytes = np.frombuffer(bytes(token_bytes), dtype=np.uint8)
+        b = np.ascontiguousarray(token_bytes, dtype=np.uint8)
+        o = np.ascontiguousarray(offsets, dtype=np.uint64)
+        self.V = len(o) - 1
+        self.W = (self.V + 31) // 32
+        self.eos_id = int(eos_id)
+        self._v = C.c_void_p()
+        _check(L.wg_vocab_create(b.ctypes.data, o.ctypes.data, self.V, self.eos_id, C.byref(self._v)))
+
+    def __del__(self):
+        if getattr(self, "_v", None):
+            load_library().wg_vocab_destroy(self._v)
+            self._v = None
+
+
+class Handle:
+    """wg_compile and the per-step calls on one set of template instances."""
+
+    def __init__(self, texts, args, vocab, flags=EOS_RESTART):
+        L = load_library()
+        c_texts, c_args, n, _keep = _marshal_templates(texts, args)
+        self.vocab = vocab                       # keeps the vocabulary alive
+        starts = np.zeros((max(n, 1), 2), dtype=np.uint32)
+        self._h = C.c_void_p()
+        _check(L.wg_compile(c_texts, c_args, n, vocab._v, flags, C.byref(self._h), starts.ctypes.data))
+        self.start_states = starts[:n]
+        self.num_states = L.wg_num_states(self._h)
+        self.W = L.wg_mask_words(self._h)
+
+    def fill_masks(self, states, bitmask, stream=None):
+        import torch
+        B = states.shape[0]
+        if tuple(states.shape) != (B, 2) or tuple(bitmask.shape) != (B, self.W):
+            raise ValueError("states must be [B, 2] and bitmask [B, W]")
+        _check(load_library().wg_fill_masks(self._h, _dev(states, torch.int32, "states"), B,
+                                            _dev(bitmask, torch.int32, "bitmask"), _stream_ptr(stream)))
+
+    def advance(self, states, tokens, stream=None):
+        import torch
+        B = states.shape[0]
+        if tuple(states.shape) != (B, 2) or tuple(tokens.shape) != (B,):
+            raise ValueError("states must be [B, 2] and tokens [B]")
+        _check(load_library().wg_advance(self._h, _dev(states, torch.int32, "states"),
+                                         _dev(tokens, torch.int32, "tokens"), B, _stream_ptr(stream)))
+
+    def cache_clear(self, stream=None):
+        _check(load_library().wg_cache_clear(self._h, _stream_ptr(stream)))
+
+    def cache_stats(self):
+        s = _Stats()
+        _check(load_library().wg_cache_stats(self._h, C.byref(s)))
+        return {k: getattr(s, k) for k, _ in _Stats._fields_}
+
+    def error_count(self):
+        n = C.c_uint64()
+        _check(load_library().wg_error_count(self._h, C.byref(n)))
+        return n.value
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            load_library().wg_destroy(self._h)
+            self._h = None
+
+
+def apply_mask(logits, bitmask, stream=None):
+    """wg_apply_mask on a [B, V] float32 or bfloat16 device tensor (rows may be strided)."""
+    import torch
+    if logits.dim() != 2 or not logits.is_cuda or logits.stride(1) != 1:
+        raise ValueError("logits must be a 2-d device tensor with unit inner stride")
+    if logits.dtype == torch.float32:
+        dt = F32
+    elif logits.dtype == torch.bfloat16:
+        dt = BF16
+    else:
+        raise ValueError("logits must be float32 or bfloat16")
+    B, V = logits.shape
+    if tuple(bitmask.shape) != (B, (V + 31) // 32):
+        raise ValueError("bitmask must be [B, ceil(V/32)]")
+    _check(load_library().wg_apply_mask(C.c_void_p(logits.data_ptr()), dt, B, V, logits.stride(0),
+                                        _dev(bitmask, torch.int32, "bitmask"), _stream_ptr(stream)))
+
+
+def select_tokens(bitmask, V, draws, tokens, stream=None):
+    """wg_select_tokens: harness sampler stand-in."""
+    import torch
+    B = bitmask.shape[0]
+    _check(load_library().wg_select_tokens(_dev(bitmask, torch.int32, "bitmask"), B, V,
+                                           _dev(draws, torch.int64, "draws"),
+                                           _dev(tokens, torch.int32, "tokens"), _stream_ptr(stream)))

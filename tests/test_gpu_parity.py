@@ -1,0 +1,227 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, bit for bit.
+
+Masks, next states and masked logits are integer / bit-pattern results, so the bar is
+exact equality everywhere (no tolerance)."""
+import numpy as np
+import pytest
+
+import wg_synth as ws
+from oracle import oracle as O
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2507_16768_amd as wg
+    wg.load_library()
+    return torch
+
+
+def _replay(torch, w, steps, check_logits_every=1, label=""):
+    """Oracle generates the trajectory; the GPU replays it step by step."""
+    import paper_2507_16768_amd as wg
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    st0 = H.start_states(o, w)
+    assert (h.start_states[w.request_template] == st0).all()
+    V, W, B = w.vocab.V, (w.vocab.V + 31) // 32, w.B
+    toks, sts, _ = o.trajectory(st0, w.token_draws(steps))
+    d_states = H.dev_states(st0)
+    d_mask = torch.empty((B, W), dtype=torch.int32, device="cuda")
+    cur = st0.copy()
+    seen = {}
+    for k in range(steps):
+        print("%s step %d" % (label, k), flush=True) if k % 16 == 0 else None
+        h.fill_masks(d_states, d_mask)
+        got = H.host_mask(d_mask)
+        for b in range(B):
+            key = (int(cur[b, 0]), int(cur[b, 1]))
+            if key not in seen:
+                seen[key] = o.mask_row(key)
+            assert (got[b] == seen[key]).all(), (label, k, b, key)
+        if k % check_logits_every == 0:
+            host = H.logits_for(w, tag=k)
+            d_log = H.dev_logits(host)
+            wg.apply_mask(d_log, d_mask)
+            want = O.apply_mask(host.copy(), np.stack([seen[(int(s[0]), int(s[1]))] for s in cur]))
+            want_bits = want.view(np.uint32) if want.dtype == np.float32 else want
+            assert (H.host_logit_bits(d_log) == want_bits).all(), (label, k)
+        d_tok = torch.from_numpy(toks[k]).cuda()
+        h.advance(d_states, d_tok)
+        cur = o.advance(cur, toks[k])
+        assert (cur == sts[k]).all()
+        assert (H.host_states(d_states) == cur).all(), (label, k)
+    assert h.error_count() == 0
+    # the cache keys a bounded Wait by its remaining budget capped at the longest token
+    return h, o, len({(k[0], o.key_rem(k)) for k in seen})
+
+
+def test_config1_tiny_full(torch_cuda):
+    """Config 1 as stated: V=32,000, one request, 64 steps, fp32 logits, argmax selection."""
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    w = ws.make_workload(1)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    cur = H.start_states(o, w)
+    d_states = H.dev_states(cur)
+    d_mask = torch.empty((1, h.W), dtype=torch.int32, device="cuda")
+    visited = set()
+    for k in range(w.steps):
+        row = o.mask_row(tuple(cur[0]))
+        h.fill_masks(d_states, d_mask)
+        assert (H.host_mask(d_mask)[0] == row).all(), k
+        host = H.logits_for(w, tag=k)
+        d_log = H.dev_logits(host)
+        wg.apply_mask(d_log, d_mask)
+        want = O.apply_mask(host.copy(), row[None, :])
+        assert (H.host_logit_bits(d_log) == want.view(np.uint32)).all(), k
+        tok = int(np.argmax(want[0]))                      # lowest index on ties
+        assert tok == int(torch.argmax(d_log[0]).item())
+        d_tok = torch.tensor([tok], dtype=torch.int32, device="cuda")
+        h.advance(d_states, d_tok)
+        cur = o.advance(cur, [tok])
+        assert (H.host_states(d_states) == cur).all(), k
+        visited.add(int(cur[0, 0]))
+    assert h.error_count() == 0 and len(visited) > 20
+
+
+@pytest.mark.parametrize("idx,V,B,steps", [
+    (2, 5003, 7, 96),        # V % 32 != 0: ragged last word and last 64-token slice
+    (3, 4099, 9, 96),
+    (4, 6001, 10, 64),
+    (5, 7013, 33, 64),
+])
+def test_reduced_configs_every_step(torch_cuda, idx, V, B, steps):
+    w = ws.make_workload(idx, V=V, B=B, steps=steps)
+    h, o, nkeys = _replay(torch_cuda, w, steps, label="cfg%d-small" % idx)
+    s = h.cache_stats()
+    assert s["lookups"] == B * steps and s["builds"] == nkeys and 0 < s["hits"] <= B * steps - nkeys
+
+
+@pytest.mark.parametrize("idx,B,steps", [(2, 64, 24), (3, 128, 16), (4, 256, 12), (5, 1024, 6)])
+def test_full_size_configs_sampled(torch_cuda, idx, B, steps):
+    """Full V and B of configs 2-5; states every step, every distinct mask, logits on 2 steps."""
+    w = ws.make_workload(idx, steps=steps)
+    assert w.B == B
+    _replay(torch_cuda, w, steps, check_logits_every=max(1, steps // 2), label="cfg%d-full" % idx)
+
+
+def test_cache_cold_warm_and_duplicates(torch_cuda):
+    torch = torch_cuda
+    w = ws.make_workload(3, V=4099, B=16, steps=4)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    st = H.start_states(o, w)                               # 16 requests in the same state
+    d_states = H.dev_states(st)
+    d_mask = torch.zeros((16, h.W), dtype=torch.int32, device="cuda")
+    want = o.mask_row(tuple(st[0]))
+    h.fill_masks(d_states, d_mask)
+    s1 = h.cache_stats()
+    assert (H.host_mask(d_mask) == want[None, :]).all()
+    assert (s1["lookups"], s1["builds"], s1["hits"]) == (16, 1, 0)
+    d_mask.zero_()
+    h.fill_masks(d_states, d_mask)
+    s2 = h.cache_stats()
+    assert (H.host_mask(d_mask) == want[None, :]).all()
+    assert (s2["lookups"], s2["builds"], s2["hits"]) == (32, 1, 16)
+    h.cache_clear()
+    d_mask.zero_()
+    h.fill_masks(d_states, d_mask)
+    s3 = h.cache_stats()
+    assert (H.host_mask(d_mask) == want[None, :]).all()
+    assert (s3["builds"], s3["hits"]) == (2, 16)
+    assert s3["keys"] >= h.num_states and s3["arena_bytes"] >= s3["keys"] * h.W * 4
+
+
+def test_error_states_and_illegal_tokens(torch_cuda):
+    torch = torch_cuda
+    w = ws.make_workload(2, V=5003, B=6, steps=1)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    s0 = int(o.start_state(0))
+    st = np.array([[s0, 0], [O.SID_ERROR, 0], [h.num_states + 5, 0], [0, 0], [s0, 0], [s0, 0]], dtype=np.uint32)
+    d_states = H.dev_states(st)
+    d_mask = torch.full((6, h.W), -1, dtype=torch.int32, device="cuda")
+    h.fill_masks(d_states, d_mask)
+    got = H.host_mask(d_mask)
+    want = o.fill_masks(st)
+    assert (got == want).all()
+    assert not got[1].any() and not got[2].any()           # ERROR / out of range: all-zero rows
+    assert got[3].sum() == 1 and got[3][0] == 1            # FINAL admits only EOS (token 0)
+    legal = int(np.nonzero(H.bits(want[0], w.vocab.V))[0][0])
+    illegal = int(np.nonzero(~H.bits(want[0], w.vocab.V))[0][5])
+    toks = np.array([legal, legal, legal, 0, illegal, w.vocab.V + 3], dtype=np.int32)
+    h.advance(d_states, torch.from_numpy(toks).cuda())
+    want_st = o.advance(st, toks)
+    assert (H.host_states(d_states) == want_st).all()
+    assert h.error_count() == 4
+    toks2 = np.array([-1, 0, 0, 0, 0, 0], dtype=np.int32)
+    h.advance(d_states, torch.from_numpy(toks2).cuda())
+    assert (H.host_states(d_states) == o.advance(want_st, toks2)).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V,stride_pad,offset", [(4096, 0, 0), (4104, 8, 0), (1000 + 13, 3, 0), (4096, 0, 1)])
+def test_apply_shapes_strides_and_special_values(torch_cuda, dtype, V, stride_pad, offset):
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    B, W = 5, (V + 31) // 32
+    x = ws.make_logits(3, B, V, 2.0)
+    x[0, 3], x[1, 4], x[2, 5], x[3, 6] = np.nan, -0.0, np.inf, 1e-42
+    m = ws.rng.draw(4, 9, np.arange(B * W)).astype(np.uint32).reshape(B, W)
+    m[4, :] = 0xFFFFFFFF
+    m[3, :] = 0
+    host = x if dtype == "f32" else ws.to_bf16_bits(x)
+    want = O.apply_mask(host.copy(), m)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    buf = torch.zeros(B * (V + stride_pad) + offset + 8, dtype=tdt, device="cuda")
+    view = buf[offset:offset + B * (V + stride_pad)].view(B, V + stride_pad)[:, :V]
+    view.copy_(H.dev_logits(host))
+    d_mask = torch.from_numpy(m.view(np.int32)).cuda()
+    wg.apply_mask(view, d_mask)
+    got = H.host_logit_bits(view.contiguous())
+    assert (got == (want.view(np.uint32) if dtype == "f32" else want)).all()
+    if stride_pad:                                           # the padding between rows is untouched
+        pad = buf[offset:offset + B * (V + stride_pad)].view(B, V + stride_pad)[:, V:]
+        assert (H.host_logit_bits(pad.contiguous()) == 0).all()
+
+
+def test_select_tokens_matches_oracle(torch_cuda):
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    B, V = 9, 5003
+    W = (V + 31) // 32
+    m = ws.rng.draw(5, 9, np.arange(B * W)).astype(np.uint32).reshape(B, W)
+    m[:, -1] &= (1 << (V % 32)) - 1
+    m[1, :] = 0
+    m[2, :] = 0
+    m[2, 77] = 1 << 9
+    draws = ws.rng.draw(6, 9, np.arange(B))
+    want = [O.select_bit(m[b], int(draws[b]) % max(1, int(H.bits(m[b], V).sum()))) if m[b].any() else -1
+            for b in range(B)]
+    d_tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    wg.select_tokens(torch.from_numpy(m.view(np.int32)).cuda(), V,
+                     torch.from_numpy(draws.view(np.int64)).cuda(), d_tok)
+    assert d_tok.cpu().tolist() == want
+
+
+def test_argument_errors_on_device_calls(torch_cuda):
+    torch = torch_cuda
+    import ctypes as C
+    import paper_2507_16768_amd as wg
+    w = ws.make_workload(1, V=2000)
+    v, h = H.make_gpu(w)
+    L = wg.load_library()
+    assert L.wg_fill_masks(h._h, None, 1, None, None) == -1
+    assert L.wg_fill_masks(h._h, C.c_void_p(16), 0, C.c_void_p(16), None) == -1
+    assert L.wg_apply_mask(C.c_void_p(16), 7, 1, 32, 32, C.c_void_p(16), None) == -1
+    assert L.wg_apply_mask(C.c_void_p(16), 0, 1, 32, 16, C.c_void_p(16), None) == -1
+    assert L.wg_advance(None, None, None, 1, None) == -1
+    assert b"null" in L.wg_last_error()
+    with pytest.raises(wg.WgError):
+        wg.Vocab(np.zeros(4, np.uint8), np.array([0, 3, 2], np.uint64), 0)

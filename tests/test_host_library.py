@@ -1,0 +1,126 @@
+"""CPU-side checks of the HIP library: it loads, exports the declared ABI, and its host
+operator compiler lowers templates to the same machine as the oracle (no kernel runs)."""
+import os
+import re
+
+import pytest
+
+import paper_2507_16768_amd as wg
+import wg_synth as ws
+from oracle import oracle as O
+from wg_synth.configs import TreeGen
+from wg_synth.rng import Counter
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+KIND = {0: "FINAL", 1: "LIT", 2: "WAIT", 3: "COND", 4: "END"}
+
+
+def test_library_exports_every_declared_symbol():
+    with open(os.path.join(ROOT, "include", "wg.h")) as f:
+        header = f.read()
+    declared = set(re.findall(r"\b(wg_[a-z_]+)\s*\(", header))
+    assert declared == set(wg.binding.EXPORTS)
+    lib = wg.load_library()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+
+
+def test_product_package_does_not_reach_for_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2507_16768_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for fn in files:
+            if fn.endswith((".py", ".cpp", ".hip", ".h")):
+                with open(os.path.join(dirpath, fn)) as f:
+                    text = f.read()
+                assert "oracle" not in text.lower(), fn
+    for fn in os.listdir(os.path.join(ROOT, "oracle")):
+        if fn.endswith((".py", ".c")):
+            with open(os.path.join(ROOT, "oracle", fn)) as f:
+                text = f.read()
+            assert "paper_2507_16768_amd" not in text and "libwgrammar" not in text, fn
+
+
+def _same_machine(texts, args, restart, lmax=8):
+    o = O.Oracle(texts, args, None, restart=restart)
+    t = wg.Table(texts, args, flags=wg.EOS_RESTART if restart else wg.EOS_STOP, lmax=lmax)
+    assert t.num_states == o.num_states
+    for i in range(len(texts)):
+        assert t.start_state(i) == o.start_state(i)
+    for sid in range(o.num_states):
+        d, s = o.describe(sid), t.state(sid)
+        assert KIND[s["kind"]] == d["kind"], sid
+        assert s["tmpl"] == d["tmpl"]
+        if d["kind"] == "LIT":
+            assert (s["byte"], s["next_a"]) == (d["byte"], d["next"])
+        if d["kind"] == "WAIT":
+            assert s["max"] == (d["max"] if d["max"] >= 0 else 0xFFFFFFFF)
+            assert s["n_keys"] == (lmax + 1 if d["max"] >= 0 else 1)
+        for x in range(257):
+            want = o.step(sid, 0, x)
+            cls = t.symbol_class(sid, x)
+            if d["kind"] == "WAIT" and d["max"] == 0 and cls == 1:
+                assert want is None                      # max=0: the class says stay, the bound says no
+            elif want is None:
+                assert cls == 0, (sid, x)
+            elif x == 256:
+                assert cls == 2 and s["eos_next"] == want[0], (sid, x)
+            elif cls == 1:
+                assert want[0] == sid, (sid, x)
+            else:
+                assert cls in (2, 3) and want[0] == (s["next_a"] if cls == 2 else s["next_b"]), (sid, x)
+    return t.num_states
+
+
+def test_lowering_matches_oracle_on_workloads():
+    for idx in (1, 2, 3):
+        w = ws.make_workload(idx)
+        _same_machine(w.texts, w.args, True, lmax=w.vocab.lmax)
+    w = ws.make_workload(4, B=6, V=1000)
+    _same_machine(w.texts, w.args, True, lmax=24)
+    w = ws.make_workload(5, B=16, V=1000)
+    assert _same_machine(w.texts, w.args, True, lmax=24) > 16 * 64
+
+
+@pytest.mark.parametrize("restart", [False, True])
+def test_lowering_matches_oracle_on_random_trees(restart, golden_dir):
+    rng = Counter(21, 2, start=7 * restart)
+    for _ in range(60):
+        trees = [TreeGen(rng, alphabet=b"ab<.", max_depth=3, write_len=(0, 3), big=False).tree(1, 20)
+                 for _ in range(rng.between(1, 3))]
+        _same_machine([ws.to_text(t) for t in trees], None, restart)
+    with open(os.path.join(golden_dir, "worked_example_template.txt")) as f:
+        text = "".join(l for l in f if not l.startswith("#"))
+    assert _same_machine([text], None, restart) == 6
+
+
+@pytest.mark.parametrize("text,frag", [
+    ("IfElse(condition=Wait(allow={a}, true_waits={x}, false_waits={x}), if_body=None, else_body=None)", "overlap"),
+    ("Sequence(Wait(allow={a}, wait={<eos>}), Write(\"b\"))", "follow"),
+    ("Wait(allow={a, <eos>}, wait={b})", "eos"),
+    ("Write($missing)", "unbound"),
+    ("Wait(allow={a})", "wait="),
+    ("Sequence(Write(\"a\")", "expected"),
+    ("Frobnicate()", "unknown operator"),
+    ("IfElse(condition=Wait(allow={}, wait={a}), if_body=None, else_body=None)", "condition"),
+    ("Wait(allow={a}, denies={b}, wait={c})", "not both"),
+    ("Write(\"a\") Write(\"b\")", "trailing"),
+    ("Sequence(Wait(allow={a}, true_waits={x}, false_waits={y}))", "only valid inside"),
+])
+def test_lowering_errors_are_reported_not_thrown(text, frag):
+    with pytest.raises(wg.WgError) as e:
+        wg.Table([text])
+    assert e.value.code == -2 and frag in str(e.value)
+
+
+def test_argument_checks_without_a_gpu():
+    with pytest.raises(wg.WgError) as e:
+        wg.Table([])
+    assert e.value.code == -1
+    with pytest.raises(wg.WgError):
+        wg.Table(['Write("a")'], flags=8)
+    with pytest.raises(ValueError):
+        wg.Table(['Write("a")', 'Write("b")'], args=[{}])
+    t = wg.Table(['Write($x)', 'Write($x)'], args=[{"x": b"ab"}, {"x": b"c"}])
+    assert t.num_states == 1 + 3 + 2 and t.start_state(1) == 4
+    with pytest.raises(wg.WgError):
+        t.state(99)

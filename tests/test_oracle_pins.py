@@ -414,7 +414,7 @@ def test_restart_and_stop_after_eos():
 
 
 @pytest.mark.parametrize("text,frag", [
-    ("Wait(allow={a}, true_waits={x}, false_waits={x})", "overlap"),
+    ("IfElse(condition=Wait(allow={a}, true_waits={x}, false_waits={x}), if_body=None, else_body=None)", "overlap"),
     ("Sequence(Wait(allow={a}, wait={<eos>}), Write(\"b\"))", "follow"),
     ("Wait(allow={a, <eos>}, wait={b})", "eos"),
     ("Write($missing)", "unbound"),
@@ -424,6 +424,9 @@ def test_restart_and_stop_after_eos():
     ("IfElse(condition=Wait(allow={}, wait={a}), if_body=None, else_body=None)", "condition"),
     ("Wait(allow={a}, denies={b}, wait={c})", "not both"),
     ("Write(\"a\") Write(\"b\")", "trailing"),
+    ("Sequence(Wait(allow={a}, true_waits={x}, false_waits={y}))", "only valid inside"),
+    ("Wait(allow={a}, true_waits={x}, false_waits={y})", "only valid inside"),
+    ("Wait(allow={a}, wait={b}, body=Wait(allow={a}, true_waits={x}, false_waits={y}))", "only valid inside"),
 ])
 def test_compile_errors(text, frag):
     with pytest.raises(O.OracleError) as e:
