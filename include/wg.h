@@ -82,8 +82,10 @@ typedef struct {
     uint64_t lookups;       /* request-steps served by wg_fill_masks */
     uint64_t hits;          /* ... whose mask was already cached */
     uint64_t builds;        /* mask rows built (one per distinct missing key) */
+    uint64_t class_scans;   /* vocabulary scans (one per distinct missing allow/wait class table) */
+    uint64_t entries_walked;/* early-exit tokens examined by the row builds */
     uint64_t keys;          /* cache keys the handle can hold (fixed at compile) */
-    uint64_t arena_bytes;   /* device bytes reserved for cached rows */
+    uint64_t arena_bytes;   /* device bytes reserved for cached rows and class indexes */
 } wg_cache_stats_t;
 
 /* State kinds reported by wg_table_state. */
@@ -161,13 +163,26 @@ int wg_apply_mask(void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V,
 int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B,
                void *stream);
 
-/* Forget every cached mask (O(1): bumps the cache epoch on the device). */
+/* Forget every cached mask row and every class-table index built from the operators' allow /
+ * wait sets (O(1): bumps the cache epoch on the device).  The static indexes of the
+ * vocabulary itself (made by wg_vocab_create) are not part of the cache. */
 int wg_cache_clear(wg_handle_t h, void *stream);
 
 /* ---- introspection (these synchronise the device) ---------------------------------------- */
 int wg_cache_stats(wg_handle_t h, wg_cache_stats_t *host_out);
 int wg_error_count(wg_handle_t h, uint64_t *host_out);
 const char *wg_last_error(void);
+
+/* ---- kernel timing (tracing aid; off by default) ------------------------------------------
+ * While enabled, wg_fill_masks and wg_advance record HIP events on the caller's stream around
+ * each of their kernels (this allocates events on the host as needed).  wg_profile_read
+ * synchronises, adds up the elapsed times since the last read and resets the record. */
+typedef struct {
+    uint64_t fill_calls, advance_calls;
+    double lookup_ms, scan_ms, build_ms, gather_ms, advance_ms;   /* summed kernel durations */
+} wg_profile_t;
+int wg_profile_enable(wg_handle_t h, int on);
+int wg_profile_read(wg_handle_t h, wg_profile_t *host_out);
 
 /* ---- sampler stand-in for harnesses (not part of the decoding path) ----------------------
  * d_tokens[b] <- index of the (d_draws[b] mod popcount)-th set bit of mask row b, or -1 for

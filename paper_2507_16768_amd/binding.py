@@ -33,7 +33,8 @@ class _Args(C.Structure):
 
 
 class _Stats(C.Structure):
-    _fields_ = [(k, C.c_uint64) for k in ("lookups", "hits", "builds", "keys", "arena_bytes")]
+    _fields_ = [(k, C.c_uint64) for k in ("lookups", "hits", "builds", "class_scans", "entries_walked", "keys",
+                                           "arena_bytes")]
 
 
 class _StateInfo(C.Structure):
@@ -41,12 +42,18 @@ class _StateInfo(C.Structure):
                                            "tmpl", "n_keys")]
 
 
+class _Profile(C.Structure):
+    _fields_ = [("fill_calls", C.c_uint64), ("advance_calls", C.c_uint64), ("lookup_ms", C.c_double),
+                ("scan_ms", C.c_double), ("build_ms", C.c_double), ("gather_ms", C.c_double),
+                ("advance_ms", C.c_double)]
+
+
 EXPORTS = [
     "wg_vocab_create", "wg_vocab_destroy", "wg_lower", "wg_table_num_states",
     "wg_table_start_state", "wg_table_state", "wg_table_symbol_class", "wg_table_destroy",
     "wg_compile", "wg_destroy", "wg_num_states", "wg_mask_words", "wg_fill_masks",
     "wg_apply_mask", "wg_advance", "wg_cache_clear", "wg_cache_stats", "wg_error_count",
-    "wg_last_error", "wg_select_tokens",
+    "wg_last_error", "wg_select_tokens", "wg_profile_enable", "wg_profile_read",
 ]
 
 
@@ -92,6 +99,8 @@ def load_library():
     L.wg_cache_stats.argtypes = [vp, C.POINTER(_Stats)]
     L.wg_error_count.argtypes = [vp, C.POINTER(u64)]
     L.wg_select_tokens.argtypes = [vp, u32, u32, vp, vp, vp]
+    L.wg_profile_enable.argtypes = [vp, C.c_int]
+    L.wg_profile_read.argtypes = [vp, C.POINTER(_Profile)]
     _lib = L
     return L
 
@@ -231,6 +240,14 @@ class Handle:
         s = _Stats()
         _check(load_library().wg_cache_stats(self._h, C.byref(s)))
         return {k: getattr(s, k) for k, _ in _Stats._fields_}
+
+    def profile_enable(self, on=True):
+        _check(load_library().wg_profile_enable(self._h, 1 if on else 0))
+
+    def profile_read(self):
+        p = _Profile()
+        _check(load_library().wg_profile_read(self._h, C.byref(p)))
+        return {k: getattr(p, k) for k, _ in _Profile._fields_}
 
     def error_count(self):
         n = C.c_uint64()

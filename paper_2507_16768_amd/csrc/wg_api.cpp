@@ -21,9 +21,16 @@ struct wg_table_s { Table t; };
 
 struct wg_vocab_s {
     DeviceVocab dv{};
-    uint8_t *d_bytes = nullptr;
-    uint32_t *d_offsets = nullptr;
+    uint8_t *d_bytes = nullptr, *d_len8 = nullptr;
+    uint32_t *d_offsets = nullptr, *d_lit_start = nullptr, *d_len_rows = nullptr;
+    uint64_t *d_chunks = nullptr;
+    ExitEntry *d_lit_entries = nullptr;
     int device = 0;
+    void release() {
+        (void)hipFree(d_bytes); (void)hipFree(d_len8); (void)hipFree(d_offsets);
+        (void)hipFree(d_lit_start); (void)hipFree(d_len_rows); (void)hipFree(d_chunks);
+        (void)hipFree(d_lit_entries);
+    }
 };
 
 struct wg_handle_s {
@@ -36,6 +43,11 @@ struct wg_handle_s {
     uint32_t max_batch = 0;
     uint32_t n_cu = 256;
     uint64_t arena_bytes = 0;
+    // kernel timing: events recorded since the last wg_profile_read
+    bool profiling = false;
+    std::vector<hipEvent_t> fill_events;       // 5 per wg_fill_masks call
+    std::vector<hipEvent_t> advance_events;    // 2 per wg_advance call
+    std::vector<hipEvent_t> spare_events;
 };
 
 namespace {
@@ -56,6 +68,17 @@ template <class T> hipError_t upload(T **dst, const T *src, size_t n) {
     return n ? hipMemcpy(*dst, src, n * sizeof(T), hipMemcpyHostToDevice) : hipSuccess;
 }
 
+hipEvent_t take_event(wg_handle_s *h) {
+    if (!h->spare_events.empty()) {
+        hipEvent_t e = h->spare_events.back();
+        h->spare_events.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+}
+
 int ensure_batch(wg_handle_s *h, uint32_t B) {
     if (B <= h->max_batch) return WG_OK;
     // grows only when a larger batch than ever before arrives (synchronises once)
@@ -64,9 +87,11 @@ int ensure_batch(wg_handle_s *h, uint32_t B) {
     WG_HIP(hipDeviceSynchronize());
     if (h->dc.key_of) (void)hipFree(h->dc.key_of);
     if (h->dc.miss) (void)hipFree(h->dc.miss);
-    h->dc.key_of = nullptr; h->dc.miss = nullptr; h->max_batch = 0;
+    if (h->dc.class_miss) (void)hipFree(h->dc.class_miss);
+    h->dc.key_of = nullptr; h->dc.miss = nullptr; h->dc.class_miss = nullptr; h->max_batch = 0;
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.key_of), nb * sizeof(uint32_t)));
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.miss), nb * sizeof(MissEntry)));
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_miss), nb * sizeof(uint32_t)));
     h->max_batch = nb;
     return WG_OK;
 }
@@ -97,27 +122,65 @@ int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uin
         if (t && off[t] - off[t - 1] > lmax) lmax = off[t] - off[t - 1];
     }
     if (host_offsets[0] != 0) return fail(WG_ERR_INVALID, "wg_vocab_create: offsets must start at 0");
+    if (lmax > 248) return fail(WG_ERR_INVALID, "wg_vocab_create: tokens longer than 248 bytes are not supported");
     std::unique_ptr<wg_vocab_s> v(new (std::nothrow) wg_vocab_s);
     if (!v) return fail(WG_ERR_NOMEM, "wg_vocab_create: out of host memory");
     WG_HIP(hipGetDevice(&v->device));
-    // 8 bytes of padding so kernels may over-read a token's tail
-    std::vector<uint8_t> bytes(total + 8, 0);
+    const uint32_t W = (V + 31u) / 32u, rs = (W + 3u) & ~3u;
+    const uint32_t n_chunks = (lmax + 7u) / 8u;
+    // Static indexes of the vocabulary (they depend on the token bytes only):
+    //  - 8 bytes of padding so kernels may over-read a token's tail
+    //  - len8 / chunks: fixed-stride view, 8 bytes per load, for the class scan
+    //  - first-byte buckets: the only tokens a literal state can admit
+    //  - per-length rows: tokens with 1 <= length <= r, for Waits with a byte budget
+    std::vector<uint8_t> bytes(total + 8, 0), len8(V, 0);
     if (total) std::memcpy(bytes.data(), host_bytes, total);
+    std::vector<uint64_t> chunks((size_t)(n_chunks ? n_chunks : 1) * V, 0);
+    std::vector<uint32_t> lit_start(257, 0), len_rows((size_t)(lmax + 2) * rs, 0);
+    for (uint32_t t = 0; t < V; t++) {
+        uint32_t L = ((int64_t)t == eos_id) ? 0u : off[t + 1] - off[t];
+        len8[t] = (uint8_t)L;
+        for (uint32_t i = 0; i < L; i++)
+            chunks[(size_t)(i / 8u) * V + t] |= (uint64_t)bytes[off[t] + i] << (8u * (i % 8u));
+        if (L) {
+            lit_start[bytes[off[t]] + 1u]++;
+            for (uint32_t r = L; r <= lmax + 1u; r++) len_rows[(size_t)r * rs + (t >> 5)] |= 1u << (t & 31u);
+        }
+    }
+    for (int y = 0; y < 256; y++) lit_start[y + 1] += lit_start[y];
+    std::vector<ExitEntry> lit_entries(lit_start[256] ? lit_start[256] : 1);
+    {
+        std::vector<uint32_t> fill(lit_start.begin(), lit_start.end() - 1);
+        for (uint32_t t = 0; t < V; t++) {
+            uint32_t L = len8[t];
+            if (!L) continue;
+            ExitEntry e;
+            e.tok = t; e.off = 1; e.cls = CLS_EXIT_A;
+            e.first = L > 1 ? bytes[off[t] + 1] : 0; e.rem = (uint8_t)(L - 1);
+            lit_entries[fill[bytes[off[t]]]++] = e;
+        }
+    }
     hipError_t e = upload(&v->d_bytes, bytes.data(), bytes.size());
     if (e == hipSuccess) e = upload(&v->d_offsets, off.data(), off.size());
+    if (e == hipSuccess) e = upload(&v->d_len8, len8.data(), len8.size());
+    if (e == hipSuccess) e = upload(&v->d_chunks, chunks.data(), chunks.size());
+    if (e == hipSuccess) e = upload(&v->d_lit_entries, lit_entries.data(), lit_entries.size());
+    if (e == hipSuccess) e = upload(&v->d_lit_start, lit_start.data(), lit_start.size());
+    if (e == hipSuccess) e = upload(&v->d_len_rows, len_rows.data(), len_rows.size());
     if (e != hipSuccess) {
-        (void)hipFree(v->d_bytes); (void)hipFree(v->d_offsets);
+        v->release();
         return fail(e == hipErrorOutOfMemory ? WG_ERR_NOMEM : WG_ERR_HIP,
                     std::string("wg_vocab_create: ") + hipGetErrorString(e));
     }
-    v->dv = DeviceVocab{v->d_bytes, v->d_offsets, V, (V + 31u) / 32u, eos_id, lmax};
+    v->dv = DeviceVocab{v->d_bytes, v->d_offsets, v->d_len8, v->d_chunks, v->d_lit_entries,
+                        v->d_lit_start, v->d_len_rows, V, W, eos_id, lmax, n_chunks, rs};
     *out = v.release();
     return WG_OK;
 }
 
 void wg_vocab_destroy(wg_vocab_t v) {
     if (!v) return;
-    (void)hipFree(v->d_bytes); (void)hipFree(v->d_offsets);
+    v->release();
     delete v;
 }
 
@@ -174,7 +237,11 @@ void wg_destroy(wg_handle_t h) {
     if (!h) return;
     (void)hipFree(h->d_states); (void)hipFree(h->d_classes); (void)hipFree(h->d_lit);
     (void)hipFree(h->dc.ctr); (void)hipFree(h->dc.built); (void)hipFree(h->dc.arena);
-    (void)hipFree(h->dc.key_of); (void)hipFree(h->dc.miss);
+    (void)hipFree(h->dc.key_of); (void)hipFree(h->dc.miss); (void)hipFree(h->dc.class_miss);
+    (void)hipFree(h->dc.class_built); (void)hipFree(h->dc.class_rows);
+    (void)hipFree(h->dc.class_entries); (void)hipFree(h->dc.class_count);
+    for (auto *v : {&h->fill_events, &h->advance_events, &h->spare_events})
+        for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
     delete h;
 }
 
@@ -201,9 +268,14 @@ int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_t
     WG_HIP(hipGetDeviceProperties(&prop, vocab->device));
     h->n_cu = prop.multiProcessorCount > 0 ? (uint32_t)prop.multiProcessorCount : 256u;
 
-    uint32_t W = vocab->dv.W;
-    uint32_t row_stride = (W + 3u) & ~3u;
-    uint64_t arena_bytes = (uint64_t)t.n_keys * row_stride * 4ull;
+    const uint32_t row_stride = vocab->dv.row_stride;
+    const uint32_t n_classes = (uint32_t)(t.classes.size() / 256);
+    if ((uint64_t)row_stride * 4ull > 160ull * 1024ull)
+        return fail(WG_ERR_INVALID, "wg_compile: a mask row does not fit the 160 KB of LDS (vocabulary too large)");
+    WG_HIP(configure_kernels(row_stride * 4u));
+    // the class index: 2 rows and up to V exit entries per class table
+    const uint64_t class_bytes = (uint64_t)n_classes * (2ull * row_stride * 4ull + (uint64_t)vocab->dv.V * sizeof(ExitEntry));
+    uint64_t arena_bytes = (uint64_t)t.n_keys * row_stride * 4ull + class_bytes;
     size_t free_b = 0, total_b = 0;
     WG_HIP(hipMemGetInfo(&free_b, &total_b));
     if (arena_bytes > (uint64_t)free_b / 2)
@@ -213,7 +285,7 @@ int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_t
     WG_HIP(upload(&h->d_states, t.states.data(), t.states.size()));
     WG_HIP(upload(&h->d_classes, t.classes.data(), t.classes.size()));
     WG_HIP(upload(&h->d_lit, t.lit.data(), t.lit.size()));
-    h->dt = DeviceTable{h->d_states, h->d_classes, h->d_lit, (uint32_t)t.states.size(), t.lmax};
+    h->dt = DeviceTable{h->d_states, h->d_classes, h->d_lit, (uint32_t)t.states.size(), t.lmax, n_classes};
 
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.ctr), sizeof(Counters)));
     Counters init{};
@@ -221,7 +293,15 @@ int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_t
     WG_HIP(hipMemcpy(h->dc.ctr, &init, sizeof init, hipMemcpyHostToDevice));
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.built), (size_t)t.n_keys * sizeof(uint32_t)));
     WG_HIP(hipMemset(h->dc.built, 0, (size_t)t.n_keys * sizeof(uint32_t)));
-    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.arena), arena_bytes ? arena_bytes : 16));
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.arena), (size_t)t.n_keys * row_stride * 4ull + 16));
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_built), n_classes * sizeof(uint32_t)));
+    WG_HIP(hipMemset(h->dc.class_built, 0, n_classes * sizeof(uint32_t)));
+    // one counter per class table, 128 bytes apart so that appends to different tables do not
+    // meet in one cache line
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_count), n_classes * 32 * sizeof(uint32_t)));
+    WG_HIP(hipMemset(h->dc.class_count, 0, n_classes * 32 * sizeof(uint32_t)));
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_rows), (size_t)n_classes * 2ull * row_stride * 4ull));
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_entries), (size_t)n_classes * vocab->dv.V * sizeof(ExitEntry)));
     h->arena_bytes = arena_bytes;
     h->dc.row_stride = row_stride;
     h->dc.n_keys = t.n_keys;
@@ -245,8 +325,10 @@ int wg_fill_masks(wg_handle_t h, const wg_state_t *d_states, uint32_t B, uint32_
     if (B == 0) return fail(WG_ERR_INVALID, "wg_fill_masks: B is 0");
     int rc = ensure_batch(h, B);
     if (rc != WG_OK) return rc;
+    hipEvent_t ev[5];
+    if (h->profiling) for (auto &e : ev) { e = take_event(h); h->fill_events.push_back(e); }
     WG_HIP(launch_fill(h->dt, h->vocab->dv, h->dc, d_states, B, d_bitmask, h->n_cu,
-                       static_cast<hipStream_t>(stream)));
+                       static_cast<hipStream_t>(stream), h->profiling ? ev : nullptr));
     return WG_OK;
 }
 
@@ -264,7 +346,15 @@ int wg_apply_mask(void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V, int6
 int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B, void *stream) {
     if (!h || !d_states || !d_tokens) return fail(WG_ERR_INVALID, "wg_advance: null argument");
     if (B == 0) return fail(WG_ERR_INVALID, "wg_advance: B is 0");
-    WG_HIP(launch_advance(h->dt, h->vocab->dv, h->dc, d_states, d_tokens, B, static_cast<hipStream_t>(stream)));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (h->profiling) {
+        e0 = take_event(h); e1 = take_event(h);
+        h->advance_events.push_back(e0); h->advance_events.push_back(e1);
+        (void)hipEventRecord(e0, s);
+    }
+    WG_HIP(launch_advance(h->dt, h->vocab->dv, h->dc, d_states, d_tokens, B, s));
+    if (h->profiling) (void)hipEventRecord(e1, s);
     return WG_OK;
 }
 
@@ -280,6 +370,7 @@ int wg_cache_stats(wg_handle_t h, wg_cache_stats_t *host_out) {
     WG_HIP(hipDeviceSynchronize());
     WG_HIP(hipMemcpy(&c, h->dc.ctr, sizeof c, hipMemcpyDeviceToHost));
     host_out->lookups = c.lookups; host_out->hits = c.hits; host_out->builds = c.builds;
+    host_out->class_scans = c.class_scans; host_out->entries_walked = c.entries_walked;
     host_out->keys = h->dc.n_keys; host_out->arena_bytes = h->arena_bytes;
     return WG_OK;
 }
@@ -290,6 +381,38 @@ int wg_error_count(wg_handle_t h, uint64_t *host_out) {
     WG_HIP(hipDeviceSynchronize());
     WG_HIP(hipMemcpy(&c, h->dc.ctr, sizeof c, hipMemcpyDeviceToHost));
     *host_out = c.errors;
+    return WG_OK;
+}
+
+int wg_profile_enable(wg_handle_t h, int on) {
+    if (!h) return fail(WG_ERR_INVALID, "wg_profile_enable: null handle");
+    h->profiling = on != 0;
+    return WG_OK;
+}
+
+int wg_profile_read(wg_handle_t h, wg_profile_t *host_out) {
+    if (!h || !host_out) return fail(WG_ERR_INVALID, "wg_profile_read: null argument");
+    WG_HIP(hipDeviceSynchronize());
+    wg_profile_t p{};
+    auto span = [](hipEvent_t a, hipEvent_t b) {
+        float ms = 0.f;
+        return (a && b && hipEventElapsedTime(&ms, a, b) == hipSuccess) ? (double)ms : 0.0;
+    };
+    for (size_t i = 0; i + 4 < h->fill_events.size(); i += 5) {
+        hipEvent_t *e = &h->fill_events[i];
+        p.lookup_ms += span(e[0], e[1]); p.scan_ms += span(e[1], e[2]);
+        p.build_ms += span(e[2], e[3]); p.gather_ms += span(e[3], e[4]);
+        p.fill_calls++;
+    }
+    for (size_t i = 0; i + 1 < h->advance_events.size(); i += 2) {
+        p.advance_ms += span(h->advance_events[i], h->advance_events[i + 1]);
+        p.advance_calls++;
+    }
+    for (auto *v : {&h->fill_events, &h->advance_events}) {
+        h->spare_events.insert(h->spare_events.end(), v->begin(), v->end());
+        v->clear();
+    }
+    *host_out = p;
     return WG_OK;
 }
 

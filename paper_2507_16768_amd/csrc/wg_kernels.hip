@@ -1,10 +1,11 @@
 // HIP kernels of the structured-decoding hot path for gfx950 (wave64).
 //
-//   lookup   : request state -> cache key, claims missing keys            (B threads)
-//   build    : one wavefront per (missing key, 64-token slice): every lane walks one
-//              token's bytes through the operator FSM, a 64-lane ballot packs the
-//              verdicts into two mask words
-//   gather   : cached row -> bitmask[b]
+//   lookup     : request state -> cache key, claims missing keys and class tables
+//   class_scan : every vocabulary token against one checkpoint's byte-class table
+//                (lane = token, table in LDS, 64-lane ballots pack the row words)
+//   key_build  : one workgroup per missing key assembles the row in LDS from the
+//                class index and the tokens that leave the state early
+//   gather     : cached row -> bitmask[b]
 //   apply    : logits <- -inf where the mask bit is 0
 //   advance  : per-request walk of the sampled token
 //   select   : harness sampler stand-in (k-th set bit of a row)
@@ -15,6 +16,9 @@
 #include "wg_device.h"
 
 namespace wg {
+
+constexpr uint32_t kScanGroup = 1024;     // tokens per class_scan workgroup
+constexpr uint32_t kCountStride = 32;     // class_count entries are 128 bytes apart
 
 // ---------------------------------------------------------------------------------------------
 // Generic per-lane walker: feeds `len` bytes at `p` to the FSM from (sid, aux).
@@ -68,6 +72,9 @@ __device__ __forceinline__ bool walk_token(const DeviceTable &T, const DeviceVoc
 }
 
 // ---------------------------------------------------------------------------------------------
+// lookup: state -> cache key.  A missing key is claimed by exactly one request (CAS on the
+// key's epoch tag) and queued for key_build; if the key's state is a checkpoint whose class
+// table has no index yet in this epoch, the table is claimed and queued for class_scan.
 __global__ void __launch_bounds__(256)
 lookup_kernel(DeviceTable T, DeviceCache Cc, const wg_state_t *__restrict__ states, uint32_t B)
 {
@@ -78,20 +85,27 @@ lookup_kernel(DeviceTable T, DeviceCache Cc, const wg_state_t *__restrict__ stat
         uint32_t key = kNoKey;
         if (sid < T.n_states) {
             const StateDesc &d = T.states[sid];
-            uint32_t variant = 0;
-            if ((d.kind_byte & 0xFFu) == WG_KIND_WAIT && d.max != WG_UNBOUNDED) {
+            uint32_t kind = d.kind_byte & 0xFFu, variant = 0;
+            if (kind == WG_KIND_WAIT && d.max != WG_UNBOUNDED) {
                 uint32_t left = d.max > aux ? d.max - aux : 0u;
                 variant = T.lmax - (left < T.lmax ? left : T.lmax);
             }
             key = d.key_base + variant;
             uint32_t epoch = Cc.ctr->epoch;
             uint32_t old = __hip_atomic_load(&Cc.built[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            hit = true;
-            if (old != epoch && atomicCAS(&Cc.built[key], old, epoch) == old) {
-                hit = false;                                // this thread owns the build
+            hit = old == epoch;
+            if (!hit && atomicCAS(&Cc.built[key], old, epoch) == old) {
                 uint32_t pos = atomicAdd(&Cc.ctr->n_miss, 1u);
                 Cc.miss[pos] = MissEntry{key, sid, aux, 0u};
-            } else if (old != epoch) hit = false;           // another request claimed it just now
+                if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
+                    uint32_t c = d.cls;
+                    uint32_t oc = __hip_atomic_load(&Cc.class_built[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (oc != epoch && atomicCAS(&Cc.class_built[c], oc, epoch) == oc) {
+                        Cc.class_count[c * kCountStride] = 0;
+                        Cc.class_miss[atomicAdd(&Cc.ctr->n_class_miss, 1u)] = c;
+                    }
+                }
+            }
         }
         Cc.key_of[b] = key;
     }
@@ -102,31 +116,293 @@ lookup_kernel(DeviceTable T, DeviceCache Cc, const wg_state_t *__restrict__ stat
     }
 }
 
-// One wavefront per (missing key, 64 consecutive tokens); work items are strided over the
-// grid so the launch size does not depend on the (device-side) number of misses.
-__global__ void __launch_bounds__(256)
-build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
+// ---------------------------------------------------------------------------------------------
+// class_scan: runs every vocabulary token through one checkpoint's class table (the part of
+// a mask that depends only on the operator's allow / wait sets, hence shared by every state
+// and request using the same sets).  Per token: the first byte that does not stay and its
+// class.  Results: row [stay] = tokens whose bytes all stay, row [end] = tokens that exit on
+// their last byte, and one ExitEntry per token that exits earlier.
+//
+// A workgroup handles one (class table, 1024-token group): the 256-byte table sits in LDS,
+// every lane owns 4 tokens (one in each of its wavefront's 4 slices of 64) whose lengths and
+// 8-byte chunks are all requested before any is used, so the loads overlap.  Exit entries are
+// appended with one atomic per workgroup.
+
+// Classifies up to 8 bytes of one chunk.  Returns true once the token is decided.
+__device__ __forceinline__ bool scan_chunk(const uint8_t *lut, uint64_t cb, uint32_t L, uint32_t k,
+                                           uint32_t &res, uint32_t &j)
 {
-    const uint32_t n_miss = Cc.ctr->n_miss;
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t slices = (Vc.V + 63u) / 64u;             // 64-token slices per row
-    const uint32_t waves_per_block = blockDim.x / 64u;
-    const uint64_t total = (uint64_t)n_miss * slices;
-    uint64_t w = (uint64_t)blockIdx.x * waves_per_block + (threadIdx.x >> 6);
-    const uint64_t stride = (uint64_t)gridDim.x * waves_per_block;
-    for (; w < total; w += stride) {
-        uint32_t m = (uint32_t)(w % n_miss), slice = (uint32_t)(w / n_miss);
-        MissEntry e = Cc.miss[m];
-        uint32_t t = slice * 64u + lane;
-        uint32_t sid = e.sid, aux = e.aux;
-        bool ok = walk_token(T, Vc, sid, aux, (int64_t)t);
-        unsigned long long bits = __ballot(ok);
-        if (lane == 0) {
-            uint32_t *row = Cc.arena + (size_t)e.key * Cc.row_stride;
-            uint32_t w0 = slice * 2u;
-            row[w0] = (uint32_t)bits;
-            if (w0 + 1u < Vc.W) row[w0 + 1u] = (uint32_t)(bits >> 32);
+    const uint32_t lo = (uint32_t)cb, hi = (uint32_t)(cb >> 32);
+    uint32_t code = 0;
+#pragma unroll
+    for (int i = 0; i < 4; i++) {
+        code |= (uint32_t)lut[(lo >> (8 * i)) & 0xFFu] << (2 * i);
+        code |= (uint32_t)lut[(hi >> (8 * i)) & 0xFFu] << (2 * i + 8);
+    }
+    const uint32_t nvalid = L - 8u * k < 8u ? L - 8u * k : 8u;
+    const uint32_t x = code ^ 0x5555u;               // a 2-bit field is 0 iff its byte stays
+    const uint32_t mm = (x | (x >> 1)) & 0x5555u & ((1u << (2u * nvalid)) - 1u);
+    if (mm) {
+        const uint32_t jj = (uint32_t)__builtin_ctz(mm) >> 1;
+        j = 8u * k + jj;
+        res = (code >> (2u * jj)) & 3u;              // 0 reject, 2 / 3 exit
+        return true;
+    }
+    if (L <= 8u * k + 8u) { res = 1u; return true; } // every byte stays
+    return false;
+}
+
+__global__ void __launch_bounds__(256)
+class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lut[256];
+    __shared__ uint32_t seg[17];                     // entries per (wave, slice), then prefix
+    const uint32_t n = Cc.ctr->n_class_miss;
+    const uint32_t groups = (Vc.V + kScanGroup - 1u) / kScanGroup;
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint64_t total = (uint64_t)n * groups;
+    const uint32_t V = Vc.V;
+    for (uint64_t item = blockIdx.x; item < total; item += gridDim.x) {
+        const uint32_t c = Cc.class_miss[(uint32_t)(item % n)];
+        const uint32_t g = (uint32_t)(item / n);
+        __syncthreads();
+        if (threadIdx.x < 64u)
+            reinterpret_cast<uint32_t *>(lut)[threadIdx.x] =
+                reinterpret_cast<const uint32_t *>(T.classes + (size_t)c * 256u)[threadIdx.x];
+        uint32_t tk[4], L[4];
+        uint64_t c0[4], c1[4], c2[4];
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            tk[s] = g * kScanGroup + (wave * 4u + s) * 64u + lane;
+            const bool valid = tk[s] < V;
+            L[s] = valid ? Vc.len8[tk[s]] : 0u;
+            c0[s] = valid ? Vc.chunks[tk[s]] : 0ull;
         }
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            c1[s] = L[s] > 8u ? Vc.chunks[(size_t)V + tk[s]] : 0ull;
+            c2[s] = L[s] > 16u ? Vc.chunks[2ull * V + tk[s]] : 0ull;
+        }
+        __syncthreads();
+        uint32_t *row_stay = Cc.class_rows + (size_t)(2u * c) * Cc.row_stride;
+        uint32_t *row_end = row_stay + Cc.row_stride;
+        uint32_t res[4], j[4];
+        unsigned long long bx[4];
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            res[s] = 0; j[s] = 0;
+            bool decided = L[s] == 0u;
+            if (!decided) decided = scan_chunk(lut, c0[s], L[s], 0, res[s], j[s]);
+            if (__any(!decided)) {
+                if (!decided) decided = scan_chunk(lut, c1[s], L[s], 1, res[s], j[s]);
+                if (__any(!decided)) {
+                    if (!decided) decided = scan_chunk(lut, c2[s], L[s], 2, res[s], j[s]);
+                    for (uint32_t k = 3; k < Vc.n_chunks && __any(!decided); k++)
+                        if (!decided) decided = scan_chunk(lut, Vc.chunks[(size_t)k * V + tk[s]], L[s], k, res[s], j[s]);
+                }
+            }
+            const bool exits = res[s] >= 2u;
+            const unsigned long long bs = __ballot(res[s] == 1u);
+            const unsigned long long be = __ballot(exits && j[s] + 1u == L[s]);
+            bx[s] = __ballot(exits && j[s] + 1u < L[s]);
+            const uint32_t w0 = (tk[s] - lane) >> 5;
+            if (lane == 0 && tk[s] < V) {
+                row_stay[w0] = (uint32_t)bs; row_end[w0] = (uint32_t)be;
+                if (w0 + 1u < Vc.W) { row_stay[w0 + 1u] = (uint32_t)(bs >> 32); row_end[w0 + 1u] = (uint32_t)(be >> 32); }
+            }
+            if (lane == 0) seg[wave * 4u + s] = (uint32_t)__popcll(bx[s]);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t sum = 0;
+            for (int i = 0; i < 16; i++) { uint32_t x = seg[i]; seg[i] = sum; sum += x; }
+            const uint32_t base = sum ? atomicAdd(&Cc.class_count[c * kCountStride], sum) : 0u;
+            for (int i = 0; i < 16; i++) seg[i] += base;
+        }
+        __syncthreads();
+        ExitEntry *out = Cc.class_entries + (size_t)c * V;
+#pragma unroll
+        for (int s = 0; s < 4; s++) {
+            if ((bx[s] >> lane) & 1ull) {
+                const uint32_t rank = (uint32_t)__popcll(bx[s] & ((1ull << lane) - 1ull));
+                const uint32_t nx = j[s] + 1u;           // index of the first remaining byte
+                uint32_t first;
+                if (nx < 24u) {
+                    const uint64_t cw = nx < 8u ? c0[s] : nx < 16u ? c1[s] : c2[s];
+                    first = (uint32_t)(cw >> (8u * (nx & 7u))) & 0xFFu;
+                } else first = Vc.bytes[Vc.offsets[tk[s]] + nx];
+                ExitEntry e;
+                e.tok = tk[s]; e.off = (uint8_t)nx; e.cls = (uint8_t)res[s];
+                e.first = (uint8_t)first; e.rem = (uint8_t)(L[s] - nx);
+                out[seg[wave * 4u + s] + rank] = e;
+            }
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&Cc.ctr->class_scans, (unsigned long long)n);
+}
+
+// ---------------------------------------------------------------------------------------------
+// key_build: one workgroup per missing state key assembles the key's mask row in LDS:
+//   (a) the context-free part from the class index (budget-limited through the per-length
+//       rows of the vocabulary), zeros for a literal / END / FINAL state;
+//   (b) the tokens that leave the state early (exit list of the class table, or the
+//       first-byte bucket of a literal state): the rest of each such token is walked from
+//       the successor state, and an accepted token sets its bit with an LDS atomic.  The two
+//       possible successors are workgroup-uniform, so their descriptors and class tables are
+//       staged in LDS and the first hop of every walk runs out of LDS and registers; only a
+//       token that leaves the successor as well continues through the table in HBM;
+//   (c) the EOS bit, then the row goes to the cache arena.
+struct HopState {                // a successor state staged for the first hop
+    uint32_t kind, lit, next_a, next_b, max;
+};
+
+__device__ __forceinline__ uint32_t token_byte(uint64_t c0, uint64_t c1, uint64_t c2, uint32_t i)
+{
+    const uint64_t cw = i < 8u ? c0 : i < 16u ? c1 : c2;
+    return (uint32_t)(cw >> (8u * (i & 7u))) & 0xFFu;
+}
+
+// Walks bytes [i, L) of a token held in registers (L <= 24) from the staged successor; hands
+// over to the generic walker when the token moves on to a third state.
+__device__ __forceinline__ bool walk_first_hop(const DeviceTable &T, const DeviceVocab &Vc,
+                                               const HopState &h, const uint8_t *lut, uint32_t tok,
+                                               uint64_t c0, uint64_t c1, uint64_t c2, uint32_t i, uint32_t L)
+{
+    uint32_t sid, aux = 0;
+    if (h.kind == WG_KIND_LIT) {
+        if (token_byte(c0, c1, c2, i) != h.lit) return false;
+        sid = h.next_a; i++;
+    } else if (h.kind == WG_KIND_WAIT || h.kind == WG_KIND_COND) {
+        for (;;) {
+            if (i >= L) return true;
+            const uint32_t c = lut[token_byte(c0, c1, c2, i)];
+            i++;
+            if (c == CLS_STAY) {
+                if (h.max != WG_UNBOUNDED) { if (aux >= h.max) return false; aux++; }
+                continue;
+            }
+            if (c == CLS_EXIT_A) { sid = h.next_a; break; }
+            if (c == CLS_EXIT_B) { sid = h.next_b; break; }
+            return false;
+        }
+        aux = 0;
+    } else return false;
+    if (i >= L) return true;
+    return walk_bytes(T, sid, aux, Vc.bytes + Vc.offsets[tok] + i, L - i);
+}
+
+__global__ void __launch_bounds__(1024)
+key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
+{
+    extern __shared__ __attribute__((aligned(16))) uint32_t row[];
+    __shared__ __attribute__((aligned(16))) uint8_t hop_lut[2][256];
+    const uint32_t n_miss = Cc.ctr->n_miss;
+    const uint32_t rs = Cc.row_stride, rs4 = rs / 4u, tid = threadIdx.x, V = Vc.V;
+    const bool regs_ok = Vc.lmax <= 24u;             // a whole token fits three 8-byte chunks
+    for (uint32_t m = blockIdx.x; m < n_miss; m += gridDim.x) {
+        const MissEntry me = Cc.miss[m];
+        const StateDesc d = T.states[me.sid];
+        const uint32_t kind = d.kind_byte & 0xFFu;
+        const ExitEntry *ents = nullptr;
+        uint32_t cnt = 0, r = Vc.lmax;
+        const uint4 *stay = nullptr, *end = nullptr;
+        if (kind == WG_KIND_LIT) {
+            const uint32_t y = (d.kind_byte >> 8) & 0xFFu;
+            ents = Vc.lit_entries + Vc.lit_start[y];
+            cnt = Vc.lit_start[y + 1u] - Vc.lit_start[y];
+        } else if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
+            ents = Cc.class_entries + (size_t)d.cls * V;
+            cnt = Cc.class_count[d.cls * kCountStride];
+            stay = reinterpret_cast<const uint4 *>(Cc.class_rows + (size_t)(2u * d.cls) * rs);
+            end = stay + rs4;
+            if (kind == WG_KIND_WAIT && d.max != WG_UNBOUNDED) {
+                const uint32_t left = d.max > me.aux ? d.max - me.aux : 0u;
+                r = left < Vc.lmax ? left : Vc.lmax;
+            }
+        }
+        // the two possible successors, staged for the first hop
+        HopState hop[2];
+#pragma unroll
+        for (int w = 0; w < 2; w++) {
+            const uint32_t t = w ? d.next_b : d.next_a;
+            hop[w] = HopState{0xFFu, 0u, WG_SID_ERROR, WG_SID_ERROR, WG_UNBOUNDED};
+            if (t < T.n_states) {
+                const StateDesc td = T.states[t];
+                hop[w] = HopState{td.kind_byte & 0xFFu, (td.kind_byte >> 8) & 0xFFu, td.next_a, td.next_b, td.max};
+                if ((hop[w].kind == WG_KIND_WAIT || hop[w].kind == WG_KIND_COND) && tid < 64u)
+                    reinterpret_cast<uint32_t *>(hop_lut[w])[tid] =
+                        reinterpret_cast<const uint32_t *>(T.classes + (size_t)td.cls * 256u)[tid];
+            }
+        }
+        // (a)
+        uint4 *row4 = reinterpret_cast<uint4 *>(row);
+        if (!stay) {
+            for (uint32_t q = tid; q < rs4; q += blockDim.x) row4[q] = uint4{0u, 0u, 0u, 0u};
+        } else if (r >= Vc.lmax) {
+            for (uint32_t q = tid; q < rs4; q += blockDim.x) {
+                const uint4 a = stay[q], b = end[q];
+                row4[q] = uint4{a.x | b.x, a.y | b.y, a.z | b.z, a.w | b.w};
+            }
+        } else {
+            // r allow-bytes may still be consumed: all-stay tokens need length <= r, tokens
+            // that exit on their last byte have length - 1 stay bytes
+            const uint4 *l0 = reinterpret_cast<const uint4 *>(Vc.len_rows + (size_t)r * rs);
+            const uint4 *l1 = l0 + rs4;
+            for (uint32_t q = tid; q < rs4; q += blockDim.x) {
+                const uint4 a = stay[q], b = end[q], x = l0[q], y = l1[q];
+                row4[q] = uint4{(a.x & x.x) | (b.x & y.x), (a.y & x.y) | (b.y & y.y),
+                                (a.z & x.z) | (b.z & y.z), (a.w & x.w) | (b.w & y.w)};
+            }
+        }
+        __syncthreads();
+        // (b) four entries per thread and pass, so their loads are in flight together
+        for (uint32_t i0 = tid; i0 < cnt; i0 += 4u * blockDim.x) {
+            ExitEntry x[4];
+            bool walk[4];
+            uint64_t c0[4], c1[4], c2[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const uint32_t i = i0 + u * blockDim.x;
+                x[u] = i < cnt ? ents[i] : ExitEntry{0u, 255u, 0u, 0u, 0u};   // off 255 fails the budget test
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const bool in_budget = (uint32_t)x[u].off - 1u <= r;
+                const HopState &h = hop[x[u].cls == CLS_EXIT_B];
+                walk[u] = in_budget && x[u].rem != 0 && !(h.kind == WG_KIND_LIT && x[u].first != h.lit);
+                if (in_budget && x[u].rem == 0) atomicOr(&row[x[u].tok >> 5], 1u << (x[u].tok & 31u));
+                c0[u] = c1[u] = c2[u] = 0;
+                if (walk[u] && regs_ok) {
+                    const uint32_t L = (uint32_t)x[u].off + x[u].rem;
+                    c0[u] = Vc.chunks[x[u].tok];
+                    if (L > 8u) c1[u] = Vc.chunks[(size_t)V + x[u].tok];
+                    if (L > 16u) c2[u] = Vc.chunks[2ull * V + x[u].tok];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                if (!walk[u]) continue;
+                const int w = x[u].cls == CLS_EXIT_B;
+                bool ok;
+                if (regs_ok) {
+                    ok = walk_first_hop(T, Vc, hop[w], hop_lut[w], x[u].tok, c0[u], c1[u], c2[u],
+                                        x[u].off, (uint32_t)x[u].off + x[u].rem);
+                } else {
+                    uint32_t sid = w ? d.next_b : d.next_a, aux = 0;
+                    ok = walk_bytes(T, sid, aux, Vc.bytes + Vc.offsets[x[u].tok] + x[u].off, x[u].rem);
+                }
+                if (ok) atomicOr(&row[x[u].tok >> 5], 1u << (x[u].tok & 31u));
+            }
+        }
+        __syncthreads();
+        if (tid == 0) atomicAdd(&Cc.ctr->entries_walked, (unsigned long long)cnt);
+        if (tid == 0 && Vc.eos_id >= 0 && d.eos_next != WG_SID_ERROR)
+            row[(uint32_t)Vc.eos_id >> 5] |= 1u << ((uint32_t)Vc.eos_id & 31u);
+        __syncthreads();
+        // (c)
+        uint4 *dst = reinterpret_cast<uint4 *>(Cc.arena + (size_t)me.key * rs);
+        for (uint32_t q = tid; q < rs4; q += blockDim.x) dst[q] = row4[q];
+        __syncthreads();
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&Cc.ctr->builds, (unsigned long long)n_miss);
 }
@@ -140,8 +416,8 @@ gather_kernel(DeviceCache Cc, uint32_t W, uint32_t *__restrict__ bitmask)
     uint32_t *dst = bitmask + (size_t)b * W;
     for (uint32_t w = blockIdx.x * blockDim.x + threadIdx.x; w < W; w += gridDim.x * blockDim.x)
         dst[w] = key == kNoKey ? 0u : src[w];
-    // the miss list has been consumed by the build that ran before this kernel
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) Cc.ctr->n_miss = 0;
+    // the miss lists have been consumed by the kernels that ran before this one
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { Cc.ctr->n_miss = 0; Cc.ctr->n_class_miss = 0; }
 }
 
 __global__ void clear_kernel(DeviceCache Cc) { Cc.ctr->epoch += 1u; }
@@ -236,18 +512,33 @@ select_kernel(const uint32_t *__restrict__ bitmask, uint32_t W, const uint64_t *
 
 static inline uint32_t cdiv(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
 
+hipError_t configure_kernels(uint32_t row_bytes)
+{
+    if (row_bytes <= 64u * 1024u) return hipSuccess;
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(key_build_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)row_bytes);
+}
+
 hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
                        const wg_state_t *states, uint32_t B, uint32_t *bitmask, uint32_t n_cu,
-                       hipStream_t s)
+                       hipStream_t s, hipEvent_t *ev)
 {
+    if (ev) (void)hipEventRecord(ev[0], s);
     lookup_kernel<<<cdiv(B, 256), 256, 0, s>>>(T, Cc, states, B);
-    uint32_t slices = (Vc.V + 63u) / 64u;
-    uint64_t max_waves = (uint64_t)B * slices;
-    uint32_t blocks = cdiv(max_waves, 4);
+    if (ev) (void)hipEventRecord(ev[1], s);
+    // the number of misses is only known on the device: both build kernels stride a fixed
+    // grid over whatever the lookup queued and fall through when nothing is queued
+    uint32_t groups = cdiv(Vc.V, kScanGroup);
+    uint64_t scan_items = (uint64_t)B * groups;
     uint32_t cap = n_cu * 8u;
-    build_kernel<<<blocks < cap ? blocks : cap, 256, 0, s>>>(T, Vc, Cc);
+    class_scan_kernel<<<scan_items < cap ? (uint32_t)scan_items : cap, 256, 0, s>>>(T, Vc, Cc);
+    if (ev) (void)hipEventRecord(ev[2], s);
+    uint32_t kb = n_cu * 2u;
+    key_build_kernel<<<B < kb ? B : kb, 1024, Cc.row_stride * 4u, s>>>(T, Vc, Cc);
+    if (ev) (void)hipEventRecord(ev[3], s);
     dim3 g(cdiv(Vc.W, 256 * 4), B);
     gather_kernel<<<g, 256, 0, s>>>(Cc, Vc.W, bitmask);
+    if (ev) (void)hipEventRecord(ev[4], s);
     return hipGetLastError();
 }
 

@@ -123,7 +123,7 @@ def test_cache_cold_warm_and_duplicates(torch_cuda):
     h.fill_masks(d_states, d_mask)
     s1 = h.cache_stats()
     assert (H.host_mask(d_mask) == want[None, :]).all()
-    assert (s1["lookups"], s1["builds"], s1["hits"]) == (16, 1, 0)
+    assert (s1["lookups"], s1["builds"], s1["hits"], s1["class_scans"]) == (16, 1, 0, 0)
     d_mask.zero_()
     h.fill_masks(d_states, d_mask)
     s2 = h.cache_stats()
@@ -135,6 +135,14 @@ def test_cache_cold_warm_and_duplicates(torch_cuda):
     s3 = h.cache_stats()
     assert (H.host_mask(d_mask) == want[None, :]).all()
     assert (s3["builds"], s3["hits"]) == (2, 16)
+    # a Wait state needs its class table scanned once per cache epoch, however many keys use it
+    wait_sid = next(s for s in range(h.num_states) if o.describe(s)["kind"] == "WAIT")
+    two = H.dev_states(np.array([[wait_sid, 0]] * 16, dtype=np.uint32))
+    h.fill_masks(two, d_mask)
+    assert (H.host_mask(d_mask) == o.mask_row((wait_sid, 0))[None, :]).all()
+    assert h.cache_stats()["class_scans"] == 1
+    h.fill_masks(two, d_mask)
+    assert h.cache_stats()["class_scans"] == 1
     assert s3["keys"] >= h.num_states and s3["arena_bytes"] >= s3["keys"] * h.W * 4
 
 
