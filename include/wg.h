@@ -164,8 +164,10 @@ int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uin
                void *stream);
 
 /* Forget every cached mask row and every class-table index built from the operators' allow /
- * wait sets (O(1): bumps the cache epoch on the device).  The static indexes of the
- * vocabulary itself (made by wg_vocab_create) are not part of the cache. */
+ * wait sets.  O(1) and launches nothing: the handle's cache generation is bumped on the host
+ * and travels with every later call as a kernel argument (so a clear recorded into a HIP
+ * graph has no effect on replays).  The static indexes of the vocabulary itself (made by
+ * wg_vocab_create) are not part of the cache. */
 int wg_cache_clear(wg_handle_t h, void *stream);
 
 /* ---- introspection (these synchronise the device) ---------------------------------------- */

@@ -289,8 +289,8 @@ int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_t
 
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.ctr), sizeof(Counters)));
     Counters init{};
-    init.epoch = 1;
     WG_HIP(hipMemcpy(h->dc.ctr, &init, sizeof init, hipMemcpyHostToDevice));
+    h->dc.epoch = 1;                                   // tags start at 0 = never built
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.built), (size_t)t.n_keys * sizeof(uint32_t)));
     WG_HIP(hipMemset(h->dc.built, 0, (size_t)t.n_keys * sizeof(uint32_t)));
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.arena), (size_t)t.n_keys * row_stride * 4ull + 16));
@@ -360,7 +360,14 @@ int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uin
 
 int wg_cache_clear(wg_handle_t h, void *stream) {
     if (!h) return fail(WG_ERR_INVALID, "wg_cache_clear: null handle");
-    WG_HIP(launch_clear(h->dc, static_cast<hipStream_t>(stream)));
+    // The generation number travels with every later launch as a kernel argument, so the
+    // clear is ordered with the caller's other calls on this handle without touching the GPU.
+    if (++h->dc.epoch == 0) {                          // wrapped: reset the tags for real
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        WG_HIP(hipMemsetAsync(h->dc.built, 0, (size_t)h->dc.n_keys * sizeof(uint32_t), s));
+        WG_HIP(hipMemsetAsync(h->dc.class_built, 0, (size_t)h->dt.n_classes * sizeof(uint32_t), s));
+        h->dc.epoch = 1;
+    }
     return WG_OK;
 }
 

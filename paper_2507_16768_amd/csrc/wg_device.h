@@ -44,10 +44,8 @@ struct DeviceVocab {
 struct MissEntry { uint32_t key, sid, aux, pad; };
 
 struct Counters {
-    uint32_t epoch;              // cache generation; built[x] == epoch <=> entry valid
     uint32_t n_miss;             // state keys to build in the call in flight
     uint32_t n_class_miss;       // class tables to scan in the call in flight
-    uint32_t pad;
     unsigned long long lookups, hits, builds, class_scans, entries_walked, errors;
 };
 
@@ -67,13 +65,13 @@ struct DeviceCache {
     uint32_t *class_miss;        // [B]
     uint32_t row_stride;         // words, multiple of 4
     uint32_t n_keys;
+    uint32_t epoch;              // cache generation of this call; tag == epoch <=> entry valid
 };
 
 // ev, when not null, holds five events recorded around the four kernels of a fill.
 hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
                        const wg_state_t *states, uint32_t B, uint32_t *bitmask, uint32_t n_cu,
                        hipStream_t s, hipEvent_t *ev);
-hipError_t launch_clear(const DeviceCache &Cc, hipStream_t s);
 hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
                         const uint32_t *bitmask, hipStream_t s);
 hipError_t launch_advance(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,

@@ -20,7 +20,7 @@ struct StateDesc {
     uint32_t next_a;      // LIT / WAIT successor, COND true target
     uint32_t next_b;      // COND false target
     uint32_t eos_next;    // state after EOS, WG_SID_ERROR if rejected
-    uint32_t cls;         // index of the state's 256-byte class table
+    uint32_t cls;         // WAIT / COND: index of the 256-byte class table; LIT: state after its Write
     uint32_t max;         // WAIT bound, WG_UNBOUNDED if none
     uint32_t key_base;    // first mask-cache key of this state
     uint32_t run;         // LIT: literal bytes from this state to the end of its Write
@@ -31,7 +31,7 @@ static_assert(sizeof(StateDesc) == 32, "descriptor layout");
 struct Table {
     std::vector<StateDesc> states;        // index = sid; [0] is FINAL
     std::vector<uint8_t> classes;         // n_class_tables * 256
-    std::vector<uint8_t> lit;             // lit[sid] = byte of a LIT state (else 0), padded by 8
+    std::vector<uint8_t> lit;             // lit[sid] = byte of a LIT state (else 0), padded by 16
     std::vector<uint32_t> tmpl;           // template instance of each state
     std::vector<uint32_t> start;          // start state of each instance
     std::vector<uint32_t> key_count;      // masks per state (1, or lmax+1 for a bounded Wait)

@@ -91,7 +91,7 @@ lookup_kernel(DeviceTable T, DeviceCache Cc, const wg_state_t *__restrict__ stat
                 variant = T.lmax - (left < T.lmax ? left : T.lmax);
             }
             key = d.key_base + variant;
-            uint32_t epoch = Cc.ctr->epoch;
+            const uint32_t epoch = Cc.epoch;
             uint32_t old = __hip_atomic_load(&Cc.built[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             hit = old == epoch;
             if (!hit && atomicCAS(&Cc.built[key], old, epoch) == old) {
@@ -420,10 +420,10 @@ gather_kernel(DeviceCache Cc, uint32_t W, uint32_t *__restrict__ bitmask)
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { Cc.ctr->n_miss = 0; Cc.ctr->n_class_miss = 0; }
 }
 
-__global__ void clear_kernel(DeviceCache Cc) { Cc.ctr->epoch += 1u; }
-
 // ---------------------------------------------------------------------------------------------
-// apply: thread = 8 consecutive tokens = one mask byte.
+// apply: thread = 8 consecutive tokens = one mask byte.  Nothing is read from the logits:
+// a group with no allowed token is overwritten with one 16-byte store per 8 bf16 (two for
+// fp32), a fully allowed group is skipped, and a mixed group stores -inf element by element.
 template <typename Vec, int kVecs, typename Elem>
 __global__ void __launch_bounds__(256)
 apply_vec_kernel(Elem *__restrict__ logits, int64_t row_stride, uint32_t V, uint32_t W,
@@ -435,14 +435,17 @@ apply_vec_kernel(Elem *__restrict__ logits, int64_t row_stride, uint32_t V, uint
     uint32_t m = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * W)[g];
     if (m == 0xFFu) return;
     Elem *p = logits + (int64_t)b * row_stride + (int64_t)g * 8;
-    union { Vec v[kVecs]; Elem e[8]; } u;
-    Vec *pv = reinterpret_cast<Vec *>(p);
+    if (m == 0u) {
+        union { Vec v[kVecs]; Elem e[8]; } u;
 #pragma unroll
-    for (int i = 0; i < kVecs; i++) u.v[i] = pv[i];
+        for (int i = 0; i < 8; i++) u.e[i] = ninf;
+        Vec *pv = reinterpret_cast<Vec *>(p);
 #pragma unroll
-    for (int i = 0; i < 8; i++) if (!((m >> i) & 1u)) u.e[i] = ninf;
+        for (int i = 0; i < kVecs; i++) pv[i] = u.v[i];
+        return;
+    }
 #pragma unroll
-    for (int i = 0; i < kVecs; i++) pv[i] = u.v[i];
+    for (int i = 0; i < 8; i++) if (!((m >> i) & 1u)) p[i] = ninf;
 }
 
 template <typename Elem>
@@ -458,16 +461,78 @@ apply_scalar_kernel(Elem *__restrict__ logits, int64_t row_stride, uint32_t V, u
 }
 
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
+// Eight bytes of a token (held as three 8-byte chunks) starting at byte i.
+__device__ __forceinline__ uint64_t token_window(uint64_t c0, uint64_t c1, uint64_t c2, uint32_t i)
+{
+    const uint32_t q = i >> 3, sh = (i & 7u) * 8u;
+    const uint64_t w0 = q == 0 ? c0 : q == 1 ? c1 : c2;
+    const uint64_t w1 = q == 0 ? c1 : q == 1 ? c2 : 0ull;
+    return sh ? (w0 >> sh) | (w1 << (64u - sh)) : w0;
+}
+
+// advance: one thread per request.  The token's bytes are fetched as 8-byte chunks (three
+// independent loads), then consumed up to eight at a time: a run of literal states is one
+// masked 8-byte compare against the state table's literal bytes, a stay-run inside a
+// checkpoint is eight independent class look-ups.  Tokens longer than 24 bytes take the
+// generic byte-at-a-time walker.
+__global__ void __launch_bounds__(64)
 advance_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, wg_state_t *__restrict__ states,
                const int32_t *__restrict__ tokens, uint32_t B)
 {
     uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
     uint32_t sid = states[b].sid, aux = states[b].aux;
-    if (walk_token(T, Vc, sid, aux, (int64_t)tokens[b])) {
-        states[b].sid = sid; states[b].aux = aux;
+    const int64_t t = (int64_t)tokens[b];
+    bool ok;
+    if (Vc.lmax > 24u || t < 0 || t >= (int64_t)Vc.V || (int64_t)Vc.eos_id == t) {
+        ok = walk_token(T, Vc, sid, aux, t);
     } else {
+        const uint32_t L = Vc.len8[t];
+        const uint64_t c0 = Vc.chunks[t];
+        const uint64_t c1 = L > 8u ? Vc.chunks[(size_t)Vc.V + t] : 0ull;
+        const uint64_t c2 = L > 16u ? Vc.chunks[2ull * Vc.V + t] : 0ull;
+        const uint64_t *lit64 = reinterpret_cast<const uint64_t *>(T.lit);
+        ok = L != 0u;
+        uint32_t i = 0;
+        while (ok && i < L) {
+            if (sid >= T.n_states) { ok = false; break; }
+            const StateDesc d = T.states[sid];
+            const uint32_t kind = d.kind_byte & 0xFFu;
+            const uint32_t n = L - i < 8u ? L - i : 8u;
+            const uint64_t tb = token_window(c0, c1, c2, i);
+            if (kind == WG_KIND_LIT) {
+                const uint32_t sh = (sid & 7u) * 8u;
+                const uint64_t l0 = lit64[sid >> 3], l1 = lit64[(sid >> 3) + 1u];
+                const uint64_t lv = sh ? (l0 >> sh) | (l1 << (64u - sh)) : l0;
+                const uint32_t m = n < d.run ? n : d.run;            // literal bytes compared now
+                const uint64_t mask = m == 8u ? ~0ull : (1ull << (8u * m)) - 1ull;
+                if ((tb ^ lv) & mask) { ok = false; break; }
+                sid = m == d.run ? d.cls : sid + m;                  // d.cls: state after the Write
+                aux = 0; i += m;
+            } else if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
+                const uint8_t *cls = T.classes + (size_t)d.cls * 256u;
+                uint32_t code = 0;
+#pragma unroll
+                for (int k = 0; k < 8; k++) code |= (uint32_t)cls[(tb >> (8 * k)) & 0xFFu] << (2 * k);
+                const uint32_t x = code ^ 0x5555u;
+                const uint32_t mm = (x | (x >> 1)) & 0x5555u & ((1u << (2u * n)) - 1u);
+                const uint32_t stays = mm ? (uint32_t)__builtin_ctz(mm) >> 1 : n;
+                if (d.max != WG_UNBOUNDED) {
+                    if (aux + stays > d.max) { ok = false; break; }
+                    aux += stays;
+                }
+                i += stays;
+                if (mm) {
+                    const uint32_t c = (code >> (2u * stays)) & 3u;
+                    if (c == CLS_REJECT) { ok = false; break; }
+                    sid = c == CLS_EXIT_A ? d.next_a : d.next_b;
+                    aux = 0; i += 1u;
+                }
+            } else { ok = false; break; }                            // FINAL / END accept no byte
+        }
+    }
+    if (ok) { states[b].sid = sid; states[b].aux = aux; }
+    else {
         states[b].sid = WG_SID_ERROR; states[b].aux = 0;
         atomicAdd(&Cc.ctr->errors, 1ull);
     }
@@ -542,12 +607,6 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
     return hipGetLastError();
 }
 
-hipError_t launch_clear(const DeviceCache &Cc, hipStream_t s)
-{
-    clear_kernel<<<1, 1, 0, s>>>(Cc);
-    return hipGetLastError();
-}
-
 hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
                         const uint32_t *bitmask, hipStream_t s)
 {
@@ -574,7 +633,7 @@ hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t
 hipError_t launch_advance(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
                           wg_state_t *states, const int32_t *tokens, uint32_t B, hipStream_t s)
 {
-    advance_kernel<<<cdiv(B, 256), 256, 0, s>>>(T, Vc, Cc, states, tokens, B);
+    advance_kernel<<<cdiv(B, 64), 64, 0, s>>>(T, Vc, Cc, states, tokens, B);
     return hipGetLastError();
 }
 

@@ -355,6 +355,7 @@ class Flattener {
                 d.next_a = (k + 1 < b.size()) ? base + static_cast<uint32_t>(k) + 1 : cont;
                 d.next_b = WG_SID_ERROR; d.eos_next = WG_SID_ERROR; d.max = WG_UNBOUNDED;
                 d.run = static_cast<uint32_t>(b.size() - k);
+                d.cls = cont;                         // LIT states reuse cls: successor of the whole run
                 t_.lit[base + k] = static_cast<uint8_t>(b[k]);
             }
             break;
@@ -441,7 +442,7 @@ void lower(const char *const *templates, const wg_args_t *args, uint32_t n, uint
             throw std::runtime_error("template " + std::to_string(i) + ": " + e.what());
         }
     }
-    t.lit.resize(t.lit.size() + 8, 0);
+    t.lit.resize(((t.lit.size() + 7) & ~size_t(7)) + 16, 0);   // whole 8-byte words past the end
     // cache keys: one mask per state, lmax+1 for a bounded Wait (one per remaining budget
     // 0..lmax; a larger budget cannot bind inside a single token)
     t.key_count.resize(t.states.size());
