@@ -105,6 +105,14 @@ def main():
     assert h.error_count() == 0, "trajectory generation fed an illegal token"
     pre = h.cache_stats()
 
+    # a plain device copy of known size (64 MiB in, 64 MiB out): the reference against which
+    # the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the other kernels are scaled
+    calib_src = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
+
     # logits ring (values are irrelevant to the work done; N(0, sigma) as the workload says)
     ring = [(torch.randn((B, V), device="cuda", dtype=torch.float32) * w.sigma).to(tdt) for _ in range(4)]
 

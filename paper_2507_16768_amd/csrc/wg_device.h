@@ -41,7 +41,21 @@ struct DeviceVocab {
     uint32_t row_stride;         // words per mask row in device arenas (multiple of 4)
 };
 
-struct MissEntry { uint32_t key, sid, aux, pad; };
+// A successor state as key_build needs it for the first hop of a walk.
+struct HopState {
+    uint32_t kind, lit, next_a, next_b, max, cls;
+};
+
+// One state key to build, resolved by the lookup so that key_build starts from a single load.
+struct MissEntry {
+    uint32_t key, sid, aux, kind;
+    uint32_t r;                  // allow-bytes that may still be consumed, capped at lmax
+    uint32_t cls;                // WAIT / COND: class table id
+    uint32_t ent_lo, ent_cnt;    // LIT: its first-byte bucket in the vocabulary's entry list
+    uint32_t eos_next, next_a, next_b, pad;
+    HopState hop[2];             // successors reached through exit A / exit B
+};
+static_assert(sizeof(MissEntry) == 96, "miss entry layout");
 
 struct Counters {
     uint32_t n_miss;             // state keys to build in the call in flight

@@ -71,12 +71,68 @@ __device__ __forceinline__ bool walk_token(const DeviceTable &T, const DeviceVoc
     return walk_bytes(T, sid, aux, Vc.bytes + lo, hi - lo);
 }
 
+// Eight bytes of a token (held as three 8-byte chunks) starting at byte i.
+__device__ __forceinline__ uint64_t token_window(uint64_t c0, uint64_t c1, uint64_t c2, uint32_t i)
+{
+    const uint32_t q = i >> 3, sh = (i & 7u) * 8u;
+    const uint64_t w0 = q == 0 ? c0 : q == 1 ? c1 : c2;
+    const uint64_t w1 = q == 0 ? c1 : q == 1 ? c2 : 0ull;
+    return sh ? (w0 >> sh) | (w1 << (64u - sh)) : w0;
+}
+
+// Walks bytes [i, L) of a token held in registers (L <= 24) from (sid, aux), consuming up to
+// eight bytes per state visit: a run of literal states is one masked 8-byte compare against
+// the state table's literal bytes, a stay-run inside a checkpoint is eight independent class
+// look-ups.  Returns false on the first rejected byte.
+__device__ __forceinline__ bool walk_chunks(const DeviceTable &T, uint32_t &sid, uint32_t &aux,
+                                            uint64_t c0, uint64_t c1, uint64_t c2, uint32_t i, uint32_t L)
+{
+    const uint64_t *lit64 = reinterpret_cast<const uint64_t *>(T.lit);
+    while (i < L) {
+        if (sid >= T.n_states) return false;
+        const StateDesc d = T.states[sid];
+        const uint32_t kind = d.kind_byte & 0xFFu;
+        const uint32_t n = L - i < 8u ? L - i : 8u;
+        const uint64_t tb = token_window(c0, c1, c2, i);
+        if (kind == WG_KIND_LIT) {
+            const uint32_t sh = (sid & 7u) * 8u;
+            const uint64_t l0 = lit64[sid >> 3], l1 = lit64[(sid >> 3) + 1u];
+            const uint64_t lv = sh ? (l0 >> sh) | (l1 << (64u - sh)) : l0;
+            const uint32_t m = n < d.run ? n : d.run;            // literal bytes compared now
+            const uint64_t mask = m == 8u ? ~0ull : (1ull << (8u * m)) - 1ull;
+            if ((tb ^ lv) & mask) return false;
+            sid = m == d.run ? d.cls : sid + m;                  // d.cls: state after the Write
+            aux = 0; i += m;
+        } else if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
+            const uint8_t *cls = T.classes + (size_t)d.cls * 256u;
+            uint32_t code = 0;
+#pragma unroll
+            for (int k = 0; k < 8; k++) code |= (uint32_t)cls[(tb >> (8 * k)) & 0xFFu] << (2 * k);
+            const uint32_t x = code ^ 0x5555u;
+            const uint32_t mm = (x | (x >> 1)) & 0x5555u & ((1u << (2u * n)) - 1u);
+            const uint32_t stays = mm ? (uint32_t)__builtin_ctz(mm) >> 1 : n;
+            if (d.max != WG_UNBOUNDED) {
+                if (aux + stays > d.max) return false;
+                aux += stays;
+            }
+            i += stays;
+            if (mm) {
+                const uint32_t c = (code >> (2u * stays)) & 3u;
+                if (c == CLS_REJECT) return false;
+                sid = c == CLS_EXIT_A ? d.next_a : d.next_b;
+                aux = 0; i += 1u;
+            }
+        } else return false;                                     // FINAL / END accept no byte
+    }
+    return true;
+}
+
 // ---------------------------------------------------------------------------------------------
 // lookup: state -> cache key.  A missing key is claimed by exactly one request (CAS on the
 // key's epoch tag) and queued for key_build; if the key's state is a checkpoint whose class
 // table has no index yet in this epoch, the table is claimed and queued for class_scan.
-__global__ void __launch_bounds__(256)
-lookup_kernel(DeviceTable T, DeviceCache Cc, const wg_state_t *__restrict__ states, uint32_t B)
+__global__ void __launch_bounds__(64)
+lookup_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, const wg_state_t *__restrict__ states, uint32_t B)
 {
     uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
     bool live = b < B, hit = false;
@@ -95,8 +151,27 @@ lookup_kernel(DeviceTable T, DeviceCache Cc, const wg_state_t *__restrict__ stat
             uint32_t old = __hip_atomic_load(&Cc.built[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             hit = old == epoch;
             if (!hit && atomicCAS(&Cc.built[key], old, epoch) == old) {
-                uint32_t pos = atomicAdd(&Cc.ctr->n_miss, 1u);
-                Cc.miss[pos] = MissEntry{key, sid, aux, 0u};
+                // this request builds the key: resolve what key_build needs into the miss entry
+                MissEntry me{};
+                me.key = key; me.sid = sid; me.aux = aux; me.kind = kind;
+                me.r = T.lmax - variant; me.cls = d.cls; me.eos_next = d.eos_next;
+                me.next_a = d.next_a; me.next_b = d.next_b;
+                if (kind == WG_KIND_LIT) {
+                    const uint32_t y = (d.kind_byte >> 8) & 0xFFu;
+                    me.ent_lo = Vc.lit_start[y];
+                    me.ent_cnt = Vc.lit_start[y + 1u] - me.ent_lo;
+                }
+#pragma unroll
+                for (int w = 0; w < 2; w++) {
+                    const uint32_t t = w ? d.next_b : d.next_a;
+                    me.hop[w] = HopState{0xFFu, 0u, WG_SID_ERROR, WG_SID_ERROR, WG_UNBOUNDED, 0u};
+                    if (t < T.n_states) {
+                        const StateDesc &td = T.states[t];
+                        me.hop[w] = HopState{td.kind_byte & 0xFFu, (td.kind_byte >> 8) & 0xFFu,
+                                             td.next_a, td.next_b, td.max, td.cls};
+                    }
+                }
+                Cc.miss[atomicAdd(&Cc.ctr->n_miss, 1u)] = me;
                 if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
                     uint32_t c = d.cls;
                     uint32_t oc = __hip_atomic_load(&Cc.class_built[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -180,8 +255,11 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
         }
 #pragma unroll
         for (int s = 0; s < 4; s++) {
-            c1[s] = L[s] > 8u ? Vc.chunks[(size_t)V + tk[s]] : 0ull;
-            c2[s] = L[s] > 16u ? Vc.chunks[2ull * V + tk[s]] : 0ull;
+            // requested regardless of the length (chunks past a token's end are zero), so that
+            // no load waits for another
+            const bool valid = tk[s] < V;
+            c1[s] = valid && Vc.n_chunks > 1u ? Vc.chunks[(size_t)V + tk[s]] : 0ull;
+            c2[s] = valid && Vc.n_chunks > 2u ? Vc.chunks[2ull * V + tk[s]] : 0ull;
         }
         __syncthreads();
         uint32_t *row_stay = Cc.class_rows + (size_t)(2u * c) * Cc.row_stride;
@@ -252,10 +330,6 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
 //       staged in LDS and the first hop of every walk runs out of LDS and registers; only a
 //       token that leaves the successor as well continues through the table in HBM;
 //   (c) the EOS bit, then the row goes to the cache arena.
-struct HopState {                // a successor state staged for the first hop
-    uint32_t kind, lit, next_a, next_b, max;
-};
-
 __device__ __forceinline__ uint32_t token_byte(uint64_t c0, uint64_t c1, uint64_t c2, uint32_t i)
 {
     const uint64_t cw = i < 8u ? c0 : i < 16u ? c1 : c2;
@@ -263,10 +337,9 @@ __device__ __forceinline__ uint32_t token_byte(uint64_t c0, uint64_t c1, uint64_
 }
 
 // Walks bytes [i, L) of a token held in registers (L <= 24) from the staged successor; hands
-// over to the generic walker when the token moves on to a third state.
-__device__ __forceinline__ bool walk_first_hop(const DeviceTable &T, const DeviceVocab &Vc,
-                                               const HopState &h, const uint8_t *lut, uint32_t tok,
-                                               uint64_t c0, uint64_t c1, uint64_t c2, uint32_t i, uint32_t L)
+// over to walk_chunks when the token moves on to a third state.
+__device__ __forceinline__ bool walk_first_hop(const DeviceTable &T, const HopState &h,
+                                               const uint8_t *lut, uint64_t c0, uint64_t c1, uint64_t c2, uint32_t i, uint32_t L)
 {
     uint32_t sid, aux = 0;
     if (h.kind == WG_KIND_LIT) {
@@ -287,8 +360,7 @@ __device__ __forceinline__ bool walk_first_hop(const DeviceTable &T, const Devic
         }
         aux = 0;
     } else return false;
-    if (i >= L) return true;
-    return walk_bytes(T, sid, aux, Vc.bytes + Vc.offsets[tok] + i, L - i);
+    return walk_chunks(T, sid, aux, c0, c1, c2, i, L);
 }
 
 __global__ void __launch_bounds__(1024)
@@ -301,39 +373,25 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
     const bool regs_ok = Vc.lmax <= 24u;             // a whole token fits three 8-byte chunks
     for (uint32_t m = blockIdx.x; m < n_miss; m += gridDim.x) {
         const MissEntry me = Cc.miss[m];
-        const StateDesc d = T.states[me.sid];
-        const uint32_t kind = d.kind_byte & 0xFFu;
+        const uint32_t kind = me.kind, r = me.r;
         const ExitEntry *ents = nullptr;
-        uint32_t cnt = 0, r = Vc.lmax;
+        uint32_t cnt = 0;
         const uint4 *stay = nullptr, *end = nullptr;
         if (kind == WG_KIND_LIT) {
-            const uint32_t y = (d.kind_byte >> 8) & 0xFFu;
-            ents = Vc.lit_entries + Vc.lit_start[y];
-            cnt = Vc.lit_start[y + 1u] - Vc.lit_start[y];
+            ents = Vc.lit_entries + me.ent_lo;
+            cnt = me.ent_cnt;
         } else if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
-            ents = Cc.class_entries + (size_t)d.cls * V;
-            cnt = Cc.class_count[d.cls * kCountStride];
-            stay = reinterpret_cast<const uint4 *>(Cc.class_rows + (size_t)(2u * d.cls) * rs);
+            ents = Cc.class_entries + (size_t)me.cls * V;
+            cnt = Cc.class_count[me.cls * kCountStride];
+            stay = reinterpret_cast<const uint4 *>(Cc.class_rows + (size_t)(2u * me.cls) * rs);
             end = stay + rs4;
-            if (kind == WG_KIND_WAIT && d.max != WG_UNBOUNDED) {
-                const uint32_t left = d.max > me.aux ? d.max - me.aux : 0u;
-                r = left < Vc.lmax ? left : Vc.lmax;
-            }
         }
-        // the two possible successors, staged for the first hop
-        HopState hop[2];
+        // the two possible successors: class tables staged in LDS for the first hop
 #pragma unroll
-        for (int w = 0; w < 2; w++) {
-            const uint32_t t = w ? d.next_b : d.next_a;
-            hop[w] = HopState{0xFFu, 0u, WG_SID_ERROR, WG_SID_ERROR, WG_UNBOUNDED};
-            if (t < T.n_states) {
-                const StateDesc td = T.states[t];
-                hop[w] = HopState{td.kind_byte & 0xFFu, (td.kind_byte >> 8) & 0xFFu, td.next_a, td.next_b, td.max};
-                if ((hop[w].kind == WG_KIND_WAIT || hop[w].kind == WG_KIND_COND) && tid < 64u)
-                    reinterpret_cast<uint32_t *>(hop_lut[w])[tid] =
-                        reinterpret_cast<const uint32_t *>(T.classes + (size_t)td.cls * 256u)[tid];
-            }
-        }
+        for (int w = 0; w < 2; w++)
+            if ((me.hop[w].kind == WG_KIND_WAIT || me.hop[w].kind == WG_KIND_COND) && tid < 64u)
+                reinterpret_cast<uint32_t *>(hop_lut[w])[tid] =
+                    reinterpret_cast<const uint32_t *>(T.classes + (size_t)me.hop[w].cls * 256u)[tid];
         // (a)
         uint4 *row4 = reinterpret_cast<uint4 *>(row);
         if (!stay) {
@@ -368,7 +426,7 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
 #pragma unroll
             for (int u = 0; u < 4; u++) {
                 const bool in_budget = (uint32_t)x[u].off - 1u <= r;
-                const HopState &h = hop[x[u].cls == CLS_EXIT_B];
+                const HopState &h = me.hop[x[u].cls == CLS_EXIT_B];
                 walk[u] = in_budget && x[u].rem != 0 && !(h.kind == WG_KIND_LIT && x[u].first != h.lit);
                 if (in_budget && x[u].rem == 0) atomicOr(&row[x[u].tok >> 5], 1u << (x[u].tok & 31u));
                 c0[u] = c1[u] = c2[u] = 0;
@@ -385,10 +443,10 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
                 const int w = x[u].cls == CLS_EXIT_B;
                 bool ok;
                 if (regs_ok) {
-                    ok = walk_first_hop(T, Vc, hop[w], hop_lut[w], x[u].tok, c0[u], c1[u], c2[u],
+                    ok = walk_first_hop(T, me.hop[w], hop_lut[w], c0[u], c1[u], c2[u],
                                         x[u].off, (uint32_t)x[u].off + x[u].rem);
                 } else {
-                    uint32_t sid = w ? d.next_b : d.next_a, aux = 0;
+                    uint32_t sid = w ? me.next_b : me.next_a, aux = 0;
                     ok = walk_bytes(T, sid, aux, Vc.bytes + Vc.offsets[x[u].tok] + x[u].off, x[u].rem);
                 }
                 if (ok) atomicOr(&row[x[u].tok >> 5], 1u << (x[u].tok & 31u));
@@ -396,7 +454,7 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
         }
         __syncthreads();
         if (tid == 0) atomicAdd(&Cc.ctr->entries_walked, (unsigned long long)cnt);
-        if (tid == 0 && Vc.eos_id >= 0 && d.eos_next != WG_SID_ERROR)
+        if (tid == 0 && Vc.eos_id >= 0 && me.eos_next != WG_SID_ERROR)
             row[(uint32_t)Vc.eos_id >> 5] |= 1u << ((uint32_t)Vc.eos_id & 31u);
         __syncthreads();
         // (c)
@@ -422,20 +480,23 @@ gather_kernel(DeviceCache Cc, uint32_t W, uint32_t *__restrict__ bitmask)
 
 // ---------------------------------------------------------------------------------------------
 // apply: thread = 8 consecutive tokens = one mask byte.  Nothing is read from the logits:
-// a group with no allowed token is overwritten with one 16-byte store per 8 bf16 (two for
-// fp32), a fully allowed group is skipped, and a mixed group stores -inf element by element.
+// a fully allowed group is skipped, a group with no allowed token is overwritten with one
+// 16-byte store per 8 bf16 (two for fp32), and a mixed group stores -inf element by element,
+// one store per disallowed token (found by count-trailing-zeros, so a group inside a
+// free-text Wait, which has one or two such tokens, issues one or two stores).
 template <typename Vec, int kVecs, typename Elem>
 __global__ void __launch_bounds__(256)
 apply_vec_kernel(Elem *__restrict__ logits, int64_t row_stride, uint32_t V, uint32_t W,
                  const uint32_t *__restrict__ bitmask, Elem ninf)
 {
-    uint32_t b = blockIdx.y;
-    uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;      // group of 8 tokens
+    const uint32_t b = blockIdx.y;
+    const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;      // group of 8 tokens
     if (g * 8u >= V) return;
-    uint32_t m = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * W)[g];
+    const uint32_t m = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * W)[g];
     if (m == 0xFFu) return;
     Elem *p = logits + (int64_t)b * row_stride + (int64_t)g * 8;
-    if (m == 0u) {
+    uint32_t z = ~m & 0xFFu;                                        // disallowed positions
+    if (z == 0xFFu) {
         union { Vec v[kVecs]; Elem e[8]; } u;
 #pragma unroll
         for (int i = 0; i < 8; i++) u.e[i] = ninf;
@@ -444,8 +505,7 @@ apply_vec_kernel(Elem *__restrict__ logits, int64_t row_stride, uint32_t V, uint
         for (int i = 0; i < kVecs; i++) pv[i] = u.v[i];
         return;
     }
-#pragma unroll
-    for (int i = 0; i < 8; i++) if (!((m >> i) & 1u)) p[i] = ninf;
+    while (z) { p[__builtin_ctz(z)] = ninf; z &= z - 1u; }
 }
 
 template <typename Elem>
@@ -461,19 +521,8 @@ apply_scalar_kernel(Elem *__restrict__ logits, int64_t row_stride, uint32_t V, u
 }
 
 // ---------------------------------------------------------------------------------------------
-// Eight bytes of a token (held as three 8-byte chunks) starting at byte i.
-__device__ __forceinline__ uint64_t token_window(uint64_t c0, uint64_t c1, uint64_t c2, uint32_t i)
-{
-    const uint32_t q = i >> 3, sh = (i & 7u) * 8u;
-    const uint64_t w0 = q == 0 ? c0 : q == 1 ? c1 : c2;
-    const uint64_t w1 = q == 0 ? c1 : q == 1 ? c2 : 0ull;
-    return sh ? (w0 >> sh) | (w1 << (64u - sh)) : w0;
-}
-
 // advance: one thread per request.  The token's bytes are fetched as 8-byte chunks (three
-// independent loads), then consumed up to eight at a time: a run of literal states is one
-// masked 8-byte compare against the state table's literal bytes, a stay-run inside a
-// checkpoint is eight independent class look-ups.  Tokens longer than 24 bytes take the
+// independent loads) and walked with walk_chunks; tokens longer than 24 bytes take the
 // generic byte-at-a-time walker.
 __global__ void __launch_bounds__(64)
 advance_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, wg_state_t *__restrict__ states,
@@ -489,47 +538,9 @@ advance_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, wg_state_t *__rest
     } else {
         const uint32_t L = Vc.len8[t];
         const uint64_t c0 = Vc.chunks[t];
-        const uint64_t c1 = L > 8u ? Vc.chunks[(size_t)Vc.V + t] : 0ull;
-        const uint64_t c2 = L > 16u ? Vc.chunks[2ull * Vc.V + t] : 0ull;
-        const uint64_t *lit64 = reinterpret_cast<const uint64_t *>(T.lit);
-        ok = L != 0u;
-        uint32_t i = 0;
-        while (ok && i < L) {
-            if (sid >= T.n_states) { ok = false; break; }
-            const StateDesc d = T.states[sid];
-            const uint32_t kind = d.kind_byte & 0xFFu;
-            const uint32_t n = L - i < 8u ? L - i : 8u;
-            const uint64_t tb = token_window(c0, c1, c2, i);
-            if (kind == WG_KIND_LIT) {
-                const uint32_t sh = (sid & 7u) * 8u;
-                const uint64_t l0 = lit64[sid >> 3], l1 = lit64[(sid >> 3) + 1u];
-                const uint64_t lv = sh ? (l0 >> sh) | (l1 << (64u - sh)) : l0;
-                const uint32_t m = n < d.run ? n : d.run;            // literal bytes compared now
-                const uint64_t mask = m == 8u ? ~0ull : (1ull << (8u * m)) - 1ull;
-                if ((tb ^ lv) & mask) { ok = false; break; }
-                sid = m == d.run ? d.cls : sid + m;                  // d.cls: state after the Write
-                aux = 0; i += m;
-            } else if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
-                const uint8_t *cls = T.classes + (size_t)d.cls * 256u;
-                uint32_t code = 0;
-#pragma unroll
-                for (int k = 0; k < 8; k++) code |= (uint32_t)cls[(tb >> (8 * k)) & 0xFFu] << (2 * k);
-                const uint32_t x = code ^ 0x5555u;
-                const uint32_t mm = (x | (x >> 1)) & 0x5555u & ((1u << (2u * n)) - 1u);
-                const uint32_t stays = mm ? (uint32_t)__builtin_ctz(mm) >> 1 : n;
-                if (d.max != WG_UNBOUNDED) {
-                    if (aux + stays > d.max) { ok = false; break; }
-                    aux += stays;
-                }
-                i += stays;
-                if (mm) {
-                    const uint32_t c = (code >> (2u * stays)) & 3u;
-                    if (c == CLS_REJECT) { ok = false; break; }
-                    sid = c == CLS_EXIT_A ? d.next_a : d.next_b;
-                    aux = 0; i += 1u;
-                }
-            } else { ok = false; break; }                            // FINAL / END accept no byte
-        }
+        const uint64_t c1 = Vc.n_chunks > 1u ? Vc.chunks[(size_t)Vc.V + t] : 0ull;
+        const uint64_t c2 = Vc.n_chunks > 2u ? Vc.chunks[2ull * Vc.V + t] : 0ull;
+        ok = L != 0u && sid < T.n_states && walk_chunks(T, sid, aux, c0, c1, c2, 0u, L);
     }
     if (ok) { states[b].sid = sid; states[b].aux = aux; }
     else {
@@ -589,7 +600,7 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
                        hipStream_t s, hipEvent_t *ev)
 {
     if (ev) (void)hipEventRecord(ev[0], s);
-    lookup_kernel<<<cdiv(B, 256), 256, 0, s>>>(T, Cc, states, B);
+    lookup_kernel<<<cdiv(B, 64), 64, 0, s>>>(T, Vc, Cc, states, B);
     if (ev) (void)hipEventRecord(ev[1], s);
     // the number of misses is only known on the device: both build kernels stride a fixed
     // grid over whatever the lookup queued and fall through when nothing is queued
