@@ -105,10 +105,11 @@ def main():
     assert h.error_count() == 0, "trajectory generation fed an illegal token"
     pre = h.cache_stats()
 
-    # a plain device copy of known size (64 MiB in, 64 MiB out): the reference against which
+    # a plain device copy of known size (512 MiB in, 512 MiB out, larger than every cache): the reference against which
     # the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the other kernels are scaled
-    calib_src = torch.zeros(64 << 20, dtype=torch.uint8, device="cuda")
+    calib_src = torch.randint(0, 255, (512 << 20,), dtype=torch.uint8, device="cuda")
     calib_dst = torch.empty_like(calib_src)
+    torch.cuda.synchronize()
     calib_dst.copy_(calib_src)
     torch.cuda.synchronize()
     del calib_src, calib_dst

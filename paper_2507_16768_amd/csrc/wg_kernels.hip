@@ -19,6 +19,7 @@ namespace wg {
 
 constexpr uint32_t kScanGroup = 1024;     // tokens per class_scan workgroup
 constexpr uint32_t kCountStride = 32;     // class_count entries are 128 bytes apart
+constexpr uint32_t kXcds = 8;             // accelerator complex dies, each with a private L2
 
 // ---------------------------------------------------------------------------------------------
 // Generic per-lane walker: feeds `len` bytes at `p` to the FSM from (sid, aux).
@@ -235,11 +236,18 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
     const uint32_t n = Cc.ctr->n_class_miss;
     const uint32_t groups = (Vc.V + kScanGroup - 1u) / kScanGroup;
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint64_t total = (uint64_t)n * groups;
     const uint32_t V = Vc.V;
-    for (uint64_t item = blockIdx.x; item < total; item += gridDim.x) {
+    // Workgroups are handed to the 8 XCDs round-robin and each XCD has its own L2.  XCD x takes
+    // the token groups g with g % 8 == x for every class table, so a group's bytes are fetched
+    // into one L2 once and then shared by all tables, instead of once per XCD.
+    const uint32_t nx = gridDim.x < kXcds ? gridDim.x : kXcds;           // a tiny grid uses fewer
+    const uint32_t xcd = blockIdx.x % nx, local = blockIdx.x / nx;
+    const uint32_t local_wgs = (gridDim.x - xcd + nx - 1u) / nx;         // workgroups on this XCD
+    const uint32_t my_groups = groups > xcd ? (groups - xcd + nx - 1u) / nx : 0u;
+    const uint64_t total = (uint64_t)n * my_groups;
+    for (uint64_t item = local; item < total; item += local_wgs) {
         const uint32_t c = Cc.class_miss[(uint32_t)(item % n)];
-        const uint32_t g = (uint32_t)(item / n);
+        const uint32_t g = (uint32_t)(item / n) * nx + xcd;
         __syncthreads();
         if (threadIdx.x < 64u)
             reinterpret_cast<uint32_t *>(lut)[threadIdx.x] =

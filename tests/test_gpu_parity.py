@@ -111,6 +111,27 @@ def test_full_size_configs_sampled(torch_cuda, idx, B, steps):
     _replay(torch_cuda, w, steps, check_logits_every=max(1, steps // 2), label="cfg%d-full" % idx)
 
 
+def test_long_tokens_take_the_generic_paths(torch_cuda):
+    """Tokens of up to 40 bytes: longer than the three 8-byte chunks the fast paths hold."""
+    import dataclasses
+    base = ws.make_workload(4, V=3001, B=12, steps=48)
+    vocab = ws.make_vocab(3001, ("geometric", 10, 40), seed=9, utf8_tenths=1)
+    assert vocab.lmax == 40
+    w = dataclasses.replace(base, vocab=vocab)
+    h, o, nkeys = _replay(torch_cuda, w, 48, label="long-tokens")
+    assert h.cache_stats()["builds"] == nkeys
+    # and a bounded Wait whose budget binds below the longest token
+    w2 = dataclasses.replace(base, vocab=vocab, B=3, request_template=np.zeros(3, dtype=np.int64),
+                             texts=['Sequence(Wait(denies={}, wait={<}, max=30), Write("ab>"))'], args=[{}])
+    o2 = H.make_oracle(w2)
+    v2, h2 = H.make_gpu(w2)
+    s = o2.start_state(0)
+    st = np.array([[s, 0], [s, 11], [s, 27]], dtype=np.uint32)
+    d_mask = torch_cuda.empty((3, h2.W), dtype=torch_cuda.int32, device="cuda")
+    h2.fill_masks(H.dev_states(st), d_mask)
+    assert (H.host_mask(d_mask) == o2.fill_masks(st)).all()
+
+
 def test_cache_cold_warm_and_duplicates(torch_cuda):
     torch = torch_cuda
     w = ws.make_workload(3, V=4099, B=16, steps=4)
