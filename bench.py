@@ -27,6 +27,20 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
+# HBM bytes per launch in the cold steps of this workload, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE (profiles/bench_config4_hbm_traffic.txt; fetch scaled x2.000, write x1.000 by
+# the counters of a 512 MiB device copy).  They describe the kernels whose source hashes to
+# TRAFFIC_SOURCE_SHA256; with any other kernel source the field is reported as null.
+TRAFFIC_BYTES = {"class_scan": None, "key_build": None, "gather": None, "apply": None}
+TRAFFIC_SOURCE_SHA256 = ""
+
+
+def kernel_source_sha256():
+    import hashlib
+    path = os.path.join(ROOT, "paper_2507_16768_amd", "csrc", "wg_kernels.hip")
+    with open(path, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()
+
 
 def cpu_baseline(w, n_steps):
     """The CPU oracle, as it stands, on the first n_steps steps of the same workload:
@@ -61,7 +75,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="workload index 1..5 (default: 4, mixed)")
-    ap.add_argument("--cpu-steps", type=int, default=16, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--cpu-steps", type=int, default=32, help="oracle steps timed for cpu_baseline (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU; --gpus %d is not supported (the path shards without "
@@ -96,14 +110,18 @@ def main():
     tokens = torch.empty((total, B), dtype=torch.int32, device="cuda")
     states = start.clone()
     mask = torch.empty((B, W), dtype=torch.int32, device="cuda")
-    n_allowed = 0
+    popcount8 = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device="cuda")
+    n_allowed = torch.zeros((), dtype=torch.int64, device="cuda")
     for k in range(total):
         h.fill_masks(states, mask)
+        if k >= Wm:                                   # allowed tokens in the timed steps' masks
+            n_allowed += popcount8[mask.view(torch.uint8).long()].sum()
         wg.select_tokens(mask, V, draws[k], tokens[k])
         h.advance(states, tokens[k])
     torch.cuda.synchronize()
     assert h.error_count() == 0, "trajectory generation fed an illegal token"
     pre = h.cache_stats()
+    disallowed_per_step = B * V - n_allowed.item() / float(K)
 
     # a plain device copy of known size (512 MiB in, 512 MiB out, larger than every cache): the reference against which
     # the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the other kernels are scaled
@@ -185,11 +203,12 @@ def main():
     entry_bytes = 8.0
     gather_bytes = B * 2 * row_bytes
     apply_dense_bytes = B * (row_bytes + 2 * esz * V)
+    apply_min_bytes = B * row_bytes + esz * disallowed_per_step      # mask in, -inf out, nothing else
     per_kernel = {
         "class_scan": (scans_per_step * scan_bytes_per_class, kt_cold["scan_us"]),
         "key_build": (builds_per_step * key_bytes_per_key + entries_per_step * entry_bytes, kt_cold["build_us"]),
         "gather": (gather_bytes, kt_cold["gather_us"]),
-        "apply": (apply_dense_bytes, apply_us),
+        "apply": (apply_min_bytes, apply_us),
     }
     dominant = max(per_kernel, key=lambda k: per_kernel[k][1])
     dom_bytes, dom_us = per_kernel[dominant]
@@ -220,9 +239,14 @@ def main():
                  "step_GBs_scan_per_key_accounting": cold_bytes / sec_cold / 1e9,
                  "frac_of_hbm_peak": cold_bytes / sec_cold / 1e9 / HBM_PEAK_GBS},
         "roofline": {"kernel": dominant, "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS, "traffic": None},
+                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,
+                     "traffic": TRAFFIC_BYTES[dominant] if kernel_source_sha256() == TRAFFIC_SOURCE_SHA256 else None,
+                     "algorithmic_bytes_per_launch": dom_bytes, "us_per_launch": dom_us},
         "kernels_us_per_step": {"cold": kt_cold, "warm": kt_warm},
         "kernels_GBs": {k: (v[0] / (v[1] * 1e-6) / 1e9 if v[1] > 0 else None) for k, v in per_kernel.items()},
+        "apply": {"disallowed_fraction": disallowed_per_step / float(B * V),
+                  "min_bytes_GBs": apply_min_bytes / (apply_us * 1e-6) / 1e9,
+                  "dense_equivalent_GBs": apply_dense_bytes / (apply_us * 1e-6) / 1e9},
         "compile_ms": compile_ms,
         "prepass": {"builds": pre["builds"], "lookups": pre["lookups"], "class_scans": pre["class_scans"]},
     }

@@ -176,8 +176,9 @@ int wg_error_count(wg_handle_t h, uint64_t *host_out);
 const char *wg_last_error(void);
 
 /* ---- kernel timing (tracing aid; off by default) ------------------------------------------
- * While enabled, wg_fill_masks and wg_advance record HIP events on the caller's stream around
- * each of their kernels (this allocates events on the host as needed).  wg_profile_read
+ * While enabled, wg_fill_masks and wg_advance launch each of their kernels with a pair of HIP
+ * events that take the kernel's own begin and end timestamps (this allocates events on the
+ * host as needed).  wg_profile_read
  * synchronises, adds up the elapsed times since the last read and resets the record. */
 typedef struct {
     uint64_t fill_calls, advance_calls;

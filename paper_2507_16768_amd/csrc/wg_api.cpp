@@ -45,7 +45,7 @@ struct wg_handle_s {
     uint64_t arena_bytes = 0;
     // kernel timing: events recorded since the last wg_profile_read
     bool profiling = false;
-    std::vector<hipEvent_t> fill_events;       // 5 per wg_fill_masks call
+    std::vector<hipEvent_t> fill_events;       // 8 per wg_fill_masks call: begin / end of each kernel
     std::vector<hipEvent_t> advance_events;    // 2 per wg_advance call
     std::vector<hipEvent_t> spare_events;
 };
@@ -325,7 +325,8 @@ int wg_fill_masks(wg_handle_t h, const wg_state_t *d_states, uint32_t B, uint32_
     if (B == 0) return fail(WG_ERR_INVALID, "wg_fill_masks: B is 0");
     int rc = ensure_batch(h, B);
     if (rc != WG_OK) return rc;
-    hipEvent_t ev[5];
+    if (B > 65535u) return fail(WG_ERR_INVALID, "wg_fill_masks: B above 65535");
+    hipEvent_t ev[8];
     if (h->profiling) for (auto &e : ev) { e = take_event(h); h->fill_events.push_back(e); }
     WG_HIP(launch_fill(h->dt, h->vocab->dv, h->dc, d_states, B, d_bitmask, h->n_cu,
                        static_cast<hipStream_t>(stream), h->profiling ? ev : nullptr));
@@ -346,15 +347,10 @@ int wg_apply_mask(void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V, int6
 int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B, void *stream) {
     if (!h || !d_states || !d_tokens) return fail(WG_ERR_INVALID, "wg_advance: null argument");
     if (B == 0) return fail(WG_ERR_INVALID, "wg_advance: B is 0");
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (h->profiling) {
-        e0 = take_event(h); e1 = take_event(h);
-        h->advance_events.push_back(e0); h->advance_events.push_back(e1);
-        (void)hipEventRecord(e0, s);
-    }
-    WG_HIP(launch_advance(h->dt, h->vocab->dv, h->dc, d_states, d_tokens, B, s));
-    if (h->profiling) (void)hipEventRecord(e1, s);
+    hipEvent_t ev[2];
+    if (h->profiling) for (auto &e : ev) { e = take_event(h); h->advance_events.push_back(e); }
+    WG_HIP(launch_advance(h->dt, h->vocab->dv, h->dc, d_states, d_tokens, B,
+                          static_cast<hipStream_t>(stream), h->profiling ? ev : nullptr));
     return WG_OK;
 }
 
@@ -405,10 +401,10 @@ int wg_profile_read(wg_handle_t h, wg_profile_t *host_out) {
         float ms = 0.f;
         return (a && b && hipEventElapsedTime(&ms, a, b) == hipSuccess) ? (double)ms : 0.0;
     };
-    for (size_t i = 0; i + 4 < h->fill_events.size(); i += 5) {
+    for (size_t i = 0; i + 7 < h->fill_events.size(); i += 8) {
         hipEvent_t *e = &h->fill_events[i];
-        p.lookup_ms += span(e[0], e[1]); p.scan_ms += span(e[1], e[2]);
-        p.build_ms += span(e[2], e[3]); p.gather_ms += span(e[3], e[4]);
+        p.lookup_ms += span(e[0], e[1]); p.scan_ms += span(e[2], e[3]);
+        p.build_ms += span(e[4], e[5]); p.gather_ms += span(e[6], e[7]);
         p.fill_calls++;
     }
     for (size_t i = 0; i + 1 < h->advance_events.size(); i += 2) {

@@ -82,14 +82,15 @@ struct DeviceCache {
     uint32_t epoch;              // cache generation of this call; tag == epoch <=> entry valid
 };
 
-// ev, when not null, holds five events recorded around the four kernels of a fill.
+// ev, when not null, holds eight events: a begin / end pair for each of the four kernels of a fill.
 hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
                        const wg_state_t *states, uint32_t B, uint32_t *bitmask, uint32_t n_cu,
                        hipStream_t s, hipEvent_t *ev);
 hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
                         const uint32_t *bitmask, hipStream_t s);
 hipError_t launch_advance(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
-                          wg_state_t *states, const int32_t *tokens, uint32_t B, hipStream_t s);
+                          wg_state_t *states, const int32_t *tokens, uint32_t B, hipStream_t s,
+                          hipEvent_t *ev);
 hipError_t launch_select(const uint32_t *bitmask, uint32_t B, uint32_t V, const uint64_t *draws,
                          int32_t *tokens, hipStream_t s);
 hipError_t configure_kernels(uint32_t row_bytes);

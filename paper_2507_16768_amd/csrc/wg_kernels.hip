@@ -12,6 +12,7 @@
 //
 // No MFMA anywhere: the path is byte matching and memory traffic.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include "wg_device.h"
 
@@ -112,7 +113,7 @@ __device__ __forceinline__ bool walk_chunks(const DeviceTable &T, uint32_t &sid,
             const uint32_t x = code ^ 0x5555u;
             const uint32_t mm = (x | (x >> 1)) & 0x5555u & ((1u << (2u * n)) - 1u);
             const uint32_t stays = mm ? (uint32_t)__builtin_ctz(mm) >> 1 : n;
-            if (d.max != WG_UNBOUNDED) {
+            if (d.max != WG_UNBOUNDED && stays) {                // each stay needs budget left
                 if (aux + stays > d.max) return false;
                 aux += stays;
             }
@@ -603,26 +604,34 @@ hipError_t configure_kernels(uint32_t row_bytes)
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)row_bytes);
 }
 
+// Launches on stream s; with a pair of events the kernel's own begin / end timestamps are
+// recorded into them (hipExtLaunchKernelGGL), which times the kernel without the queue gaps
+// that events recorded between launches would include.
+template <typename K, typename... A>
+static inline void launch(K kernel, dim3 grid, dim3 block, uint32_t lds, hipStream_t s, hipEvent_t *ev,
+                          A... args)
+{
+    if (ev) hipExtLaunchKernelGGL(kernel, grid, block, lds, s, ev[0], ev[1], 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
+}
+
 hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
                        const wg_state_t *states, uint32_t B, uint32_t *bitmask, uint32_t n_cu,
                        hipStream_t s, hipEvent_t *ev)
 {
-    if (ev) (void)hipEventRecord(ev[0], s);
-    lookup_kernel<<<cdiv(B, 64), 64, 0, s>>>(T, Vc, Cc, states, B);
-    if (ev) (void)hipEventRecord(ev[1], s);
+    launch(lookup_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s, ev, T, Vc, Cc, states, B);
     // the number of misses is only known on the device: both build kernels stride a fixed
     // grid over whatever the lookup queued and fall through when nothing is queued
     uint32_t groups = cdiv(Vc.V, kScanGroup);
     uint64_t scan_items = (uint64_t)B * groups;
     uint32_t cap = n_cu * 8u;
-    class_scan_kernel<<<scan_items < cap ? (uint32_t)scan_items : cap, 256, 0, s>>>(T, Vc, Cc);
-    if (ev) (void)hipEventRecord(ev[2], s);
+    launch(class_scan_kernel, dim3(scan_items < cap ? (uint32_t)scan_items : cap), dim3(256), 0, s,
+           ev ? ev + 2 : nullptr, T, Vc, Cc);
     uint32_t kb = n_cu * 2u;
-    key_build_kernel<<<B < kb ? B : kb, 1024, Cc.row_stride * 4u, s>>>(T, Vc, Cc);
-    if (ev) (void)hipEventRecord(ev[3], s);
-    dim3 g(cdiv(Vc.W, 256 * 4), B);
-    gather_kernel<<<g, 256, 0, s>>>(Cc, Vc.W, bitmask);
-    if (ev) (void)hipEventRecord(ev[4], s);
+    launch(key_build_kernel, dim3(B < kb ? B : kb), dim3(1024), Cc.row_stride * 4u, s,
+           ev ? ev + 4 : nullptr, T, Vc, Cc);
+    launch(gather_kernel, dim3(cdiv(Vc.W, 256 * 4), B), dim3(256), 0, s, ev ? ev + 6 : nullptr, Cc, Vc.W,
+           bitmask);
     return hipGetLastError();
 }
 
@@ -650,9 +659,10 @@ hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t
 }
 
 hipError_t launch_advance(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
-                          wg_state_t *states, const int32_t *tokens, uint32_t B, hipStream_t s)
+                          wg_state_t *states, const int32_t *tokens, uint32_t B, hipStream_t s,
+                          hipEvent_t *ev)
 {
-    advance_kernel<<<cdiv(B, 64), 64, 0, s>>>(T, Vc, Cc, states, tokens, B);
+    launch(advance_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s, ev, T, Vc, Cc, states, tokens, B);
     return hipGetLastError();
 }
 

@@ -132,6 +132,82 @@ def test_long_tokens_take_the_generic_paths(torch_cuda):
     assert (H.host_mask(d_mask) == o2.fill_masks(st)).all()
 
 
+def _all_states(o):
+    out = [[O.SID_ERROR, 0]]
+    for sid in range(o.num_states):
+        d = o.describe(sid)
+        auxes = range(0, d["max"] + 2) if d["kind"] == "WAIT" and d["max"] >= 0 else (0,)
+        out += [[sid, a] for a in auxes]
+    return np.array(out, dtype=np.uint32)
+
+
+@pytest.mark.parametrize("restart", [False, True])
+def test_random_trees_every_state_every_token(torch_cuda, restart):
+    """Exhaustive on tiny inputs: every (state, budget) mask and every (state, token) advance of
+    random operator trees (None bodies, empty Writes, max=0, nested loops) on a vocabulary of
+    all strings up to length 3 over four letters, EOS in the middle of the id range."""
+    from wg_synth.configs import TreeGen
+    from wg_synth.rng import Counter
+    from wg_synth.vocab import from_tokens
+    import itertools
+    import paper_2507_16768_amd as wg
+    torch = torch_cuda
+    alpha = b"ab<."
+    toks = [bytes(t) for n in (1, 2, 3) for t in itertools.product(alpha, repeat=n)]
+    toks.insert(17, b"")                                   # EOS is token 17
+    toks.insert(40, b"")                                   # a byte-less token that is not EOS
+    vocab = from_tokens(toks, eos_id=17)
+    ov = O.OracleVocab(vocab.bytes, vocab.offsets, vocab.eos_id)
+    gv = wg.Vocab(vocab.bytes, vocab.offsets, vocab.eos_id)
+    rng = Counter(31, 2, start=500 * restart)
+    V = vocab.V
+    n_states = 0
+    for case in range(40):
+        trees = [TreeGen(rng, alphabet=alpha, max_depth=3, write_len=(0, 3), big=False).tree(1, 18)
+                 for _ in range(rng.between(1, 3))]
+        texts = [ws.to_text(t) for t in trees]
+        o = O.Oracle(texts, None, ov, restart=restart)
+        h = wg.Handle(texts, None, gv, flags=wg.EOS_RESTART if restart else wg.EOS_STOP)
+        st = _all_states(o)
+        n_states += len(st)
+        d_mask = torch.empty((len(st), h.W), dtype=torch.int32, device="cuda")
+        h.fill_masks(H.dev_states(st), d_mask)
+        want = o.fill_masks(st)
+        assert (H.host_mask(d_mask) == want).all(), texts
+        rep = np.repeat(st, V, axis=0)
+        tk = np.tile(np.arange(V, dtype=np.int32), len(st))
+        d_st = H.dev_states(rep)
+        h.advance(d_st, torch.from_numpy(tk).cuda())
+        got = H.host_states(d_st)
+        want_st = o.advance(rep, tk)
+        bad = np.nonzero((got != want_st).any(axis=1))[0]
+        assert len(bad) == 0, (texts, rep[bad[0]], toks[tk[bad[0]]], got[bad[0]], want_st[bad[0]])
+        ok = got[:, 0] != O.SID_ERROR
+        assert (ok.reshape(len(st), V) == np.stack([H.bits(r, V) for r in want])).all()
+    assert n_states > 400
+
+
+def test_tiny_shapes_and_no_eos(torch_cuda):
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    from wg_synth.vocab import from_tokens
+    for V in (1, 31, 33, 64, 65):
+        toks = [bytes([97 + (i % 3)]) * (1 + i % 5) for i in range(V)]
+        vocab = from_tokens(toks, eos_id=-1)
+        o = O.Oracle(['Sequence(Wait(allow={a}, wait={b}, max=3), Write("c"))'], None,
+                     O.OracleVocab(vocab.bytes, vocab.offsets, -1), restart=True)
+        gv = wg.Vocab(vocab.bytes, vocab.offsets, -1)
+        h = wg.Handle(['Sequence(Wait(allow={a}, wait={b}, max=3), Write("c"))'], None, gv)
+        st = _all_states(o)
+        d_mask = torch.full((len(st), h.W), -1, dtype=torch.int32, device="cuda")
+        h.fill_masks(H.dev_states(st), d_mask)
+        assert (H.host_mask(d_mask) == o.fill_masks(st)).all(), V
+        x = ws.make_logits(1, len(st), V, 1.0)
+        d_log = H.dev_logits(x)
+        wg.apply_mask(d_log, d_mask)
+        assert (H.host_logit_bits(d_log) == O.apply_mask(x.copy(), o.fill_masks(st)).view(np.uint32)).all()
+
+
 def test_cache_cold_warm_and_duplicates(torch_cuda):
     torch = torch_cuda
     w = ws.make_workload(3, V=4099, B=16, steps=4)
