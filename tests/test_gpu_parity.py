@@ -132,6 +132,46 @@ def test_long_tokens_take_the_generic_paths(torch_cuda):
     assert (H.host_mask(d_mask) == o2.fill_masks(st)).all()
 
 
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
+def test_full_trajectories_reproduce_oracle_digests(torch_cuda, idx, golden_dir):
+    """Every config at its full B, V and step count: the GPU draws the whole trajectory from its
+    own masks (fill, pick the (draw mod popcount)-th allowed token, advance); tokens and states
+    must hash, block by block, to the digests the oracle-only script wrote."""
+    import hashlib
+    import json
+    import os
+    import paper_2507_16768_amd as wg
+    torch = torch_cuda
+    with open(os.path.join(golden_dir, "trajectory_digests.json")) as f:
+        gold = json.load(f)[str(idx)]
+    w = ws.make_workload(idx)
+    assert (gold["steps"], gold["B"], gold["V"]) == (w.steps, w.B, w.vocab.V) and gold["errors"] == 0
+    v, h = H.make_gpu(w)
+    states = H.dev_states(h.start_states[w.request_template])
+    mask = torch.empty((w.B, h.W), dtype=torch.int32, device="cuda")
+    draws = torch.from_numpy(w.token_draws().view(np.int64)).cuda()
+    toks = torch.empty((w.steps, w.B), dtype=torch.int32, device="cuda")
+    sts = torch.empty((w.steps, w.B, 2), dtype=torch.int32, device="cuda")
+    for k in range(w.steps):
+        if k % 512 == 0:
+            print("cfg%d trajectory step %d" % (idx, k), flush=True)
+        h.fill_masks(states, mask)
+        wg.select_tokens(mask, w.vocab.V, draws[k], toks[k])
+        h.advance(states, toks[k])
+        sts[k].copy_(states)
+    torch.cuda.synchronize()
+    assert h.error_count() == 0
+    toks_h, sts_h = toks.cpu().numpy(), sts.cpu().numpy().view(np.uint32)
+    blk = gold["block"]
+    for i, want in enumerate(gold["digests"]):
+        d = hashlib.sha256()
+        d.update(np.ascontiguousarray(toks_h[i * blk:(i + 1) * blk], dtype="<i4").tobytes())
+        d.update(np.ascontiguousarray(sts_h[i * blk:(i + 1) * blk], dtype="<u4").tobytes())
+        assert d.hexdigest()[:16] == want, "config %d diverges from the oracle in steps %d..%d" % (idx, i * blk, (i + 1) * blk - 1)
+    s = h.cache_stats()
+    assert s["builds"] == gold["distinct_masks"] and s["lookups"] == w.steps * w.B
+
+
 def _all_states(o):
     out = [[O.SID_ERROR, 0]]
     for sid in range(o.num_states):
