@@ -78,8 +78,9 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=32, help="oracle steps timed for cpu_baseline (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU; --gpus %d is not supported (the path shards without "
-              "collectives, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        print("bench.py measures one GPU; --gpus %d is not supported (the path shards by request or "
+              "by vocabulary slice without collectives, so more GPUs add nothing to measure here)"
+              % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import torch
@@ -195,7 +196,7 @@ def main():
     apply_us = 1e3 * e0.elapsed_time(e1) / K
     kt_cold["apply_us"] = kt_warm["apply_us"] = apply_us
 
-    # ---- algorithmic bytes (per unit figures are derived in the design doc) ----
+    # ---- algorithmic bytes per launch of each kernel ----
     sum_len = int(w.vocab.offsets[-1])
     row_bytes = V / 8.0
     scan_bytes_per_class = sum_len + V + 2 * row_bytes        # token bytes + length byte + two rows
@@ -215,8 +216,8 @@ def main():
     dom_gbs = dom_bytes / (dom_us * 1e-6) / 1e9 if dom_us > 0 else 0.0
     # whole-step accounting in the terms the throughput target is stated in: one streamed pass
     # over the vocabulary per built key, the gather, and the dense read-modify-write of apply
-    survey_build_bytes_per_key = sum_len + V + row_bytes
-    cold_bytes = builds_per_step * survey_build_bytes_per_key + gather_bytes + apply_dense_bytes
+    scan_per_key_bytes = sum_len + V + row_bytes
+    cold_bytes = builds_per_step * scan_per_key_bytes + gather_bytes + apply_dense_bytes
     warm_bytes = gather_bytes + apply_dense_bytes
 
     out = {
