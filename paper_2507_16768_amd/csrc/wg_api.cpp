@@ -1,6 +1,7 @@
 // C ABI: handles, device uploads, argument checks, kernel launches.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstring>
 #include <memory>
 #include <new>
@@ -148,16 +149,23 @@ int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uin
         }
     }
     for (int y = 0; y < 256; y++) lit_start[y + 1] += lit_start[y];
+    // Within a bucket the entries are ordered by remaining length, so that the lanes of a
+    // wavefront walk remainders of similar length.
     std::vector<ExitEntry> lit_entries(lit_start[256] ? lit_start[256] : 1);
     {
-        std::vector<uint32_t> fill(lit_start.begin(), lit_start.end() - 1);
-        for (uint32_t t = 0; t < V; t++) {
-            uint32_t L = len8[t];
-            if (!L) continue;
+        std::vector<uint32_t> order;
+        order.reserve(V);
+        for (uint32_t t = 0; t < V; t++) if (len8[t]) order.push_back(t);
+        std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+            const uint32_t fa = bytes[off[a]], fb = bytes[off[b]];
+            return fa != fb ? fa < fb : len8[a] < len8[b];
+        });
+        for (size_t i = 0; i < order.size(); i++) {
+            const uint32_t t = order[i], L = len8[t];
             ExitEntry e;
             e.tok = t; e.off = 1; e.cls = CLS_EXIT_A;
             e.first = L > 1 ? bytes[off[t] + 1] : 0; e.rem = (uint8_t)(L - 1);
-            lit_entries[fill[bytes[off[t]]]++] = e;
+            lit_entries[i] = e;
         }
     }
     hipError_t e = upload(&v->d_bytes, bytes.data(), bytes.size());

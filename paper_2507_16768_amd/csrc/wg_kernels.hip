@@ -21,6 +21,7 @@ namespace wg {
 constexpr uint32_t kScanGroup = 1024;     // tokens per class_scan workgroup
 constexpr uint32_t kCountStride = 32;     // class_count entries are 128 bytes apart
 constexpr uint32_t kXcds = 8;             // accelerator complex dies, each with a private L2
+constexpr uint32_t kShortRem = 4;         // exit entries with at most this many bytes left are "short"
 
 // ---------------------------------------------------------------------------------------------
 // Generic per-lane walker: feeds `len` bytes at `p` to the FSM from (sid, aux).
@@ -178,7 +179,8 @@ lookup_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, const wg_state_t *_
                     uint32_t c = d.cls;
                     uint32_t oc = __hip_atomic_load(&Cc.class_built[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if (oc != epoch && atomicCAS(&Cc.class_built[c], oc, epoch) == oc) {
-                        Cc.class_count[c * kCountStride] = 0;
+                        Cc.class_count[c * kCountStride] = 0;          // short entries, from the front
+                        Cc.class_count[c * kCountStride + 1u] = 0;     // long entries, from the back
                         Cc.class_miss[atomicAdd(&Cc.ctr->n_class_miss, 1u)] = c;
                     }
                 }
@@ -233,7 +235,7 @@ __global__ void __launch_bounds__(256)
 class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lut[256];
-    __shared__ uint32_t seg[17];                     // entries per (wave, slice), then prefix
+    __shared__ uint32_t seg[2][17];                  // short / long entries per (wave, slice), then offsets
     const uint32_t n = Cc.ctr->n_class_miss;
     const uint32_t groups = (Vc.V + kScanGroup - 1u) / kScanGroup;
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
@@ -274,7 +276,7 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
         uint32_t *row_stay = Cc.class_rows + (size_t)(2u * c) * Cc.row_stride;
         uint32_t *row_end = row_stay + Cc.row_stride;
         uint32_t res[4], j[4];
-        unsigned long long bx[4];
+        unsigned long long bx[4], by[4];
 #pragma unroll
         for (int s = 0; s < 4; s++) {
             res[s] = 0; j[s] = 0;
@@ -291,27 +293,36 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
             const bool exits = res[s] >= 2u;
             const unsigned long long bs = __ballot(res[s] == 1u);
             const unsigned long long be = __ballot(exits && j[s] + 1u == L[s]);
-            bx[s] = __ballot(exits && j[s] + 1u < L[s]);
+            const bool early = exits && j[s] + 1u < L[s];
+            const bool is_long = L[s] - j[s] - 1u > kShortRem;
+            bx[s] = __ballot(early && !is_long);
+            by[s] = __ballot(early && is_long);
             const uint32_t w0 = (tk[s] - lane) >> 5;
             if (lane == 0 && tk[s] < V) {
                 row_stay[w0] = (uint32_t)bs; row_end[w0] = (uint32_t)be;
                 if (w0 + 1u < Vc.W) { row_stay[w0 + 1u] = (uint32_t)(bs >> 32); row_end[w0 + 1u] = (uint32_t)(be >> 32); }
             }
-            if (lane == 0) seg[wave * 4u + s] = (uint32_t)__popcll(bx[s]);
+            if (lane == 0) { seg[0][wave * 4u + s] = (uint32_t)__popcll(bx[s]); seg[1][wave * 4u + s] = (uint32_t)__popcll(by[s]); }
         }
         __syncthreads();
-        if (threadIdx.x == 0) {
+        // Entries with a short remainder fill the class's list from the front, the others from
+        // the back, so that a wavefront of key_build walks remainders of similar length.
+        if (threadIdx.x < 2u) {
+            const uint32_t side = threadIdx.x;
             uint32_t sum = 0;
-            for (int i = 0; i < 16; i++) { uint32_t x = seg[i]; seg[i] = sum; sum += x; }
-            const uint32_t base = sum ? atomicAdd(&Cc.class_count[c * kCountStride], sum) : 0u;
-            for (int i = 0; i < 16; i++) seg[i] += base;
+            for (int i = 0; i < 16; i++) { uint32_t x = seg[side][i]; seg[side][i] = sum; sum += x; }
+            const uint32_t base = sum ? atomicAdd(&Cc.class_count[c * kCountStride + side], sum) : 0u;
+            for (int i = 0; i < 16; i++) seg[side][i] += base;
+            seg[side][16] = sum;
         }
         __syncthreads();
         ExitEntry *out = Cc.class_entries + (size_t)c * V;
 #pragma unroll
         for (int s = 0; s < 4; s++) {
-            if ((bx[s] >> lane) & 1ull) {
-                const uint32_t rank = (uint32_t)__popcll(bx[s] & ((1ull << lane) - 1ull));
+            const bool sh = (bx[s] >> lane) & 1ull, lg = (by[s] >> lane) & 1ull;
+            if (sh || lg) {
+                const unsigned long long mine = sh ? bx[s] : by[s];
+                const uint32_t rank = (uint32_t)__popcll(mine & ((1ull << lane) - 1ull));
                 const uint32_t nx = j[s] + 1u;           // index of the first remaining byte
                 uint32_t first;
                 if (nx < 24u) {
@@ -321,7 +332,8 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
                 ExitEntry e;
                 e.tok = tk[s]; e.off = (uint8_t)nx; e.cls = (uint8_t)res[s];
                 e.first = (uint8_t)first; e.rem = (uint8_t)(L[s] - nx);
-                out[seg[wave * 4u + s] + rank] = e;
+                const uint32_t pos = seg[sh ? 0 : 1][wave * 4u + s] + rank;
+                out[sh ? pos : V - 1u - pos] = e;
             }
         }
     }
@@ -384,14 +396,16 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
         const MissEntry me = Cc.miss[m];
         const uint32_t kind = me.kind, r = me.r;
         const ExitEntry *ents = nullptr;
-        uint32_t cnt = 0;
+        uint32_t cnt = 0, n_front = 0xFFFFFFFFu, back = 0;
         const uint4 *stay = nullptr, *end = nullptr;
         if (kind == WG_KIND_LIT) {
             ents = Vc.lit_entries + me.ent_lo;
             cnt = me.ent_cnt;
         } else if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
             ents = Cc.class_entries + (size_t)me.cls * V;
-            cnt = Cc.class_count[me.cls * kCountStride];
+            n_front = Cc.class_count[me.cls * kCountStride];
+            cnt = n_front + Cc.class_count[me.cls * kCountStride + 1u];
+            back = V - cnt;                           // index i >= n_front lives at i + back
             stay = reinterpret_cast<const uint4 *>(Cc.class_rows + (size_t)(2u * me.cls) * rs);
             end = stay + rs4;
         }
@@ -430,7 +444,7 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
 #pragma unroll
             for (int u = 0; u < 4; u++) {
                 const uint32_t i = i0 + u * blockDim.x;
-                x[u] = i < cnt ? ents[i] : ExitEntry{0u, 255u, 0u, 0u, 0u};   // off 255 fails the budget test
+                x[u] = i < cnt ? ents[i < n_front ? i : i + back] : ExitEntry{0u, 255u, 0u, 0u, 0u};   // off 255 fails the budget test
             }
 #pragma unroll
             for (int u = 0; u < 4; u++) {
