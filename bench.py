@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # WRITE_SIZE (profiles/bench_config4_hbm_traffic.txt; fetch scaled x2.000, write x1.000 by
 # the counters of a 512 MiB device copy).  They describe the kernels whose source hashes to
 # TRAFFIC_SOURCE_SHA256; with any other kernel source the field is reported as null.
-TRAFFIC_BYTES = {"class_scan": None, "key_build": None, "gather": None, "apply": None}
-TRAFFIC_SOURCE_SHA256 = ""
+TRAFFIC_BYTES = {"class_scan": 3.86e6, "key_build": 9.02e6, "gather": 10.38e6, "apply": 58.76e6}
+TRAFFIC_SOURCE_SHA256 = "f61e62a0c53215ef9bfbf1b611b4278e12799ebfd1a699cbdaf2d871ed8eeb91"
 
 
 def kernel_source_sha256():
