@@ -196,6 +196,39 @@ def main():
     apply_us = 1e3 * e0.elapsed_time(e1) / K
     kt_cold["apply_us"] = kt_warm["apply_us"] = apply_us
 
+    # ---- greedy variant of the step: fill, masked argmax (logits only read), advance ----
+    greedy_tok = torch.empty(B, dtype=torch.int32, device="cuda")
+
+    def run_greedy(cold, n):
+        for k in range(n):
+            if cold:
+                h.cache_clear()
+            h.fill_masks(states, mask)
+            wg.masked_argmax(fresh[k & 3], mask, greedy_tok)
+            h.advance(states, greedy_tok)
+
+    def timed_greedy(cold):
+        states.copy_(start)
+        h.cache_clear()
+        run_greedy(cold, Wm)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        run_greedy(cold, K)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / K
+
+    fresh = [(torch.randn((B, V), device="cuda", dtype=torch.float32) * w.sigma).to(tdt) for _ in range(4)]
+    sec_greedy_cold = timed_greedy(True)
+    sec_greedy_warm = timed_greedy(False)      # revisits the states of the run before it
+    assert h.error_count() == 0, "greedy decoding chose an illegal token"
+    torch.cuda.synchronize()
+    e0.record()
+    for k in range(K):
+        wg.masked_argmax(fresh[k & 3], mask, greedy_tok)
+    e1.record()
+    torch.cuda.synchronize()
+    argmax_us = 1e3 * e0.elapsed_time(e1) / K
+
     # ---- algorithmic bytes per launch of each kernel ----
     sum_len = int(w.vocab.offsets[-1])
     row_bytes = V / 8.0
@@ -248,6 +281,11 @@ def main():
         "apply": {"disallowed_fraction": disallowed_per_step / float(B * V),
                   "min_bytes_GBs": apply_min_bytes / (apply_us * 1e-6) / 1e9,
                   "dense_equivalent_GBs": apply_dense_bytes / (apply_us * 1e-6) / 1e9},
+        "greedy": {"note": "fill + wg_masked_argmax + advance; logits are read, never written",
+                   "cold_ms_per_step": sec_greedy_cold * 1e3, "warm_ms_per_step": sec_greedy_warm * 1e3,
+                   "cold_request_steps_per_s": B / sec_greedy_cold, "warm_request_steps_per_s": B / sec_greedy_warm,
+                   "masked_argmax_us": argmax_us,
+                   "masked_argmax_dense_read_GBs": B * (row_bytes + esz * V) / (argmax_us * 1e-6) / 1e9},
         "compile_ms": compile_ms,
         "prepass": {"builds": pre["builds"], "lookups": pre["lookups"], "class_scans": pre["class_scans"]},
     }

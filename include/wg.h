@@ -157,6 +157,17 @@ int wg_fill_masks(wg_handle_t h, const wg_state_t *d_states, uint32_t B, uint32_
 int wg_apply_mask(void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V,
                   int64_t row_stride_elems, const uint32_t *d_bitmask, void *stream);
 
+/* wg_masked_argmax: greedy decoding fused with the mask, the step that follows mask application
+ * when sampling is greedy: d_tokens[b] <- the allowed token of row b with the largest logit.  The
+ * logits are only read (nothing is set to -inf), so this call replaces wg_apply_mask + argmax.
+ * A NaN ranks below every number (also below -inf), equal values (-0.0 equals +0.0) keep the
+ * lowest token id, a row that allows nothing gives -1.  Layout of logits and mask as in
+ * wg_apply_mask.  The workgroups of a row merge through a per-GPU scratch array inside the
+ * library, so two wg_masked_argmax calls must not overlap on one GPU (order them on one stream). */
+int wg_masked_argmax(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V,
+                     int64_t row_stride_elems, const uint32_t *d_bitmask, int32_t *d_tokens,
+                     void *stream);
+
 /* wg_advance: d_states[b] <- state after d_tokens[b] (state tracking, constant work per
  * symbol).  A token the state rejects, or a token id outside [0, V), gives
  * {WG_SID_ERROR, 0} and increments the handle's device error counter. */

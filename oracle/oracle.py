@@ -64,6 +64,7 @@ def lib():
         L.wgo_mask_row.argtypes = [C.c_void_p, C.POINTER(_Vocab), C.c_uint32, C.c_uint32, C.c_void_p]
         L.wgo_fill_masks.argtypes = [C.c_void_p, C.POINTER(_Vocab), C.c_void_p, C.c_uint32, C.c_void_p]
         L.wgo_apply_mask.argtypes = [C.c_void_p, C.c_int, C.c_uint32, C.c_uint32, C.c_int64, C.c_void_p]
+        L.wgo_masked_argmax.argtypes = [C.c_void_p, C.c_int, C.c_uint32, C.c_uint32, C.c_int64, C.c_void_p, C.c_void_p]
         L.wgo_advance.argtypes = [C.c_void_p, C.POINTER(_Vocab), C.c_void_p, C.c_void_p, C.c_uint32]
         L.wgo_key_rem.restype = C.c_uint32
         L.wgo_key_rem.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32]
@@ -212,6 +213,18 @@ def apply_mask(logits, bitmask, row_stride=None):
     assert bm.shape == (B, (V + 31) // 32)
     lib().wgo_apply_mask(logits.ctypes.data, dt, B, V, stride, bm.ctypes.data)
     return logits
+
+
+def masked_argmax(logits, bitmask):
+    """int32 [B]: greedy token per row of a float32 array or a uint16 array of bfloat16 bits."""
+    assert logits.flags["C_CONTIGUOUS"] and logits.ndim == 2
+    B, V = logits.shape
+    bm = np.ascontiguousarray(bitmask, dtype=np.uint32)
+    assert bm.shape == (B, (V + 31) // 32)
+    dt = {np.dtype(np.float32): 0, np.dtype(np.uint16): 1}[logits.dtype]
+    out = np.zeros(B, dtype=np.int32)
+    lib().wgo_masked_argmax(logits.ctypes.data, dt, B, V, V, bm.ctypes.data, out.ctypes.data)
+    return out
 
 
 def select_bit(row, k):

@@ -696,6 +696,37 @@ void wgo_apply_mask(void *logits, int dtype, uint32_t B, uint32_t V, int64_t row
         }
 }
 
+/* Greedy choice over the allowed tokens, logits untouched: tokens_out[b] = the allowed token
+ * with the largest logit; a NaN ranks below every number (also below -inf), equal values
+ * (-0.0 equals +0.0) keep the lowest token id; -1 if the row allows nothing. */
+static double elem_value(const void *logits, int dtype, int64_t idx)
+{
+    if (dtype == 0) { float f; memcpy(&f, (const char *)logits + 4 * idx, 4); return (double)f; }
+    uint32_t u = (uint32_t)((const uint16_t *)logits)[idx] << 16;       /* bfloat16 -> float32, exact */
+    float f; memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+void wgo_masked_argmax(const void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
+                       const uint32_t *bitmask, int32_t *tokens_out)
+{
+    uint32_t W = (V + 31u) / 32u;
+    for (uint32_t b = 0; b < B; b++) {
+        int64_t best = -1; double best_v = 0.0; int best_nan = 1;
+        for (uint32_t t = 0; t < V; t++) {
+            if (!((bitmask[(size_t)b * W + (t >> 5)] >> (t & 31)) & 1u)) continue;
+            double v = elem_value(logits, dtype, (int64_t)b * row_stride + t);
+            int is_nan = v != v;
+            int better;
+            if (best < 0) better = 1;
+            else if (best_nan) better = !is_nan;                  /* any number beats a NaN */
+            else better = !is_nan && v > best_v;
+            if (better) { best = t; best_v = v; best_nan = is_nan; }
+        }
+        tokens_out[b] = (int32_t)best;
+    }
+}
+
 /* states[b] <- state after tokens[b]; a rejected or out-of-range token gives ERROR. */
 void wgo_advance(const wgo_handle *h, const wgo_vocab *v, uint32_t *states /*[B][2]*/,
                  const int32_t *tokens, uint32_t B)

@@ -53,7 +53,7 @@ EXPORTS = [
     "wg_table_start_state", "wg_table_state", "wg_table_symbol_class", "wg_table_destroy",
     "wg_compile", "wg_destroy", "wg_num_states", "wg_mask_words", "wg_fill_masks",
     "wg_apply_mask", "wg_advance", "wg_cache_clear", "wg_cache_stats", "wg_error_count",
-    "wg_last_error", "wg_select_tokens", "wg_profile_enable", "wg_profile_read",
+    "wg_last_error", "wg_select_tokens", "wg_profile_enable", "wg_profile_read", "wg_masked_argmax",
 ]
 
 
@@ -95,6 +95,7 @@ def load_library():
     L.wg_fill_masks.argtypes = [vp, vp, u32, vp, vp]
     L.wg_apply_mask.argtypes = [vp, C.c_int, u32, u32, i64, vp, vp]
     L.wg_advance.argtypes = [vp, vp, vp, u32, vp]
+    L.wg_masked_argmax.argtypes = [vp, C.c_int, u32, u32, i64, vp, vp, vp]
     L.wg_cache_clear.argtypes = [vp, vp]
     L.wg_cache_stats.argtypes = [vp, C.POINTER(_Stats)]
     L.wg_error_count.argtypes = [vp, C.POINTER(u64)]
@@ -276,6 +277,22 @@ def apply_mask(logits, bitmask, stream=None):
         raise ValueError("bitmask must be [B, ceil(V/32)]")
     _check(load_library().wg_apply_mask(C.c_void_p(logits.data_ptr()), dt, B, V, logits.stride(0),
                                         _dev(bitmask, torch.int32, "bitmask"), _stream_ptr(stream)))
+
+
+def masked_argmax(logits, bitmask, tokens, stream=None):
+    """wg_masked_argmax on a [B, V] float32 or bfloat16 device tensor; tokens is int32 [B]."""
+    import torch
+    if logits.dim() != 2 or not logits.is_cuda or logits.stride(1) != 1:
+        raise ValueError("logits must be a 2-d device tensor with unit inner stride")
+    dt = {torch.float32: F32, torch.bfloat16: BF16}.get(logits.dtype)
+    if dt is None:
+        raise ValueError("logits must be float32 or bfloat16")
+    B, V = logits.shape
+    if tuple(bitmask.shape) != (B, (V + 31) // 32) or tuple(tokens.shape) != (B,):
+        raise ValueError("bitmask must be [B, ceil(V/32)] and tokens [B]")
+    _check(load_library().wg_masked_argmax(C.c_void_p(logits.data_ptr()), dt, B, V, logits.stride(0),
+                                           _dev(bitmask, torch.int32, "bitmask"),
+                                           _dev(tokens, torch.int32, "tokens"), _stream_ptr(stream)))
 
 
 def select_tokens(bitmask, V, draws, tokens, stream=None):

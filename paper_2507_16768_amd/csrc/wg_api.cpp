@@ -352,6 +352,18 @@ int wg_apply_mask(void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V, int6
     return WG_OK;
 }
 
+int wg_masked_argmax(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V,
+                     int64_t row_stride_elems, const uint32_t *d_bitmask, int32_t *d_tokens, void *stream) {
+    if (!d_logits || !d_bitmask || !d_tokens) return fail(WG_ERR_INVALID, "wg_masked_argmax: null argument");
+    if (B == 0 || V == 0) return fail(WG_ERR_INVALID, "wg_masked_argmax: empty batch or vocabulary");
+    if (dtype != WG_F32 && dtype != WG_BF16) return fail(WG_ERR_INVALID, "wg_masked_argmax: unknown dtype");
+    if (row_stride_elems < (int64_t)V) return fail(WG_ERR_INVALID, "wg_masked_argmax: row stride smaller than V");
+    if (B > 65535u) return fail(WG_ERR_INVALID, "wg_masked_argmax: B above 65535");
+    WG_HIP(launch_masked_argmax(d_logits, dtype, B, V, row_stride_elems, d_bitmask, d_tokens,
+                                static_cast<hipStream_t>(stream)));
+    return WG_OK;
+}
+
 int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B, void *stream) {
     if (!h || !d_states || !d_tokens) return fail(WG_ERR_INVALID, "wg_advance: null argument");
     if (B == 0) return fail(WG_ERR_INVALID, "wg_advance: B is 0");

@@ -88,6 +88,8 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
                        hipStream_t s, hipEvent_t *ev);
 hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
                         const uint32_t *bitmask, hipStream_t s);
+hipError_t launch_masked_argmax(const void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
+                                const uint32_t *bitmask, int32_t *tokens, hipStream_t s);
 hipError_t launch_advance(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
                           wg_state_t *states, const int32_t *tokens, uint32_t B, hipStream_t s,
                           hipEvent_t *ev);

@@ -531,6 +531,140 @@ apply_vec_kernel(Elem *__restrict__ logits, int64_t row_stride, uint32_t V, uint
     while (z) { p[__builtin_ctz(z)] = ninf; z &= z - 1u; }
 }
 
+// masked argmax: a row is split over several workgroups; a thread takes 32-token groups (one mask word and up
+// to four 16-byte loads for bf16, eight for fp32), skips pieces with no allowed token without
+// touching their logits, and keeps its best candidate as a 64-bit key: the logit mapped to an unsigned
+// integer that orders like the number (NaN lowest, -0 folded into +0) in the high half, the
+// complement of the token id in the low half, so that a plain maximum prefers the larger logit
+// and then the lower id.  Key 0 means "no allowed token".  Workgroups merge their maxima with
+// one 64-bit atomic max per row; the workgroup of a row that finishes last writes the token id.
+__device__ __forceinline__ uint32_t order_key(uint32_t u)      // float bits -> orderable integer
+{
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0u;               // NaN
+    if ((u << 1) == 0u) u = 0u;                                    // -0.0 == +0.0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float elem_float(uint32_t raw) { return __uint_as_float(raw); }
+__device__ __forceinline__ float elem_float(uint16_t raw) { return __uint_as_float((uint32_t)raw << 16); }  // bfloat16
+
+// Per-row merge area of masked argmax, shared by the workgroups of a row: the running maximum
+// of the keys and the number of workgroups that have reported.  File-scope device memory: all
+// zero between calls (the last workgroup of a row clears what it reads), one copy per GPU, so
+// two masked-argmax calls that overlap on one GPU would mix their rows.
+constexpr uint32_t kArgmaxRows = 65536;
+constexpr int kArgmaxPieces = 8;           // 16-byte pieces of logits per thread of masked_argmax
+__device__ unsigned long long g_argmax_key[kArgmaxRows];
+
+// The maximum over the allowed tokens of one 16-byte piece, folded into four accumulators.
+// A disallowed token's bits are forced to all ones, which is a NaN in both formats, and the
+// hardware maximum ignores NaNs, so NaN logits drop out the same way.
+__device__ __forceinline__ void piece_max(const uint4 &v, uint32_t m, uint16_t, float acc[4])
+{
+    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+    const uint32_t nm = ~m;
+#pragma unroll
+    for (int k = 0; k < 4; k++) {                     // dword k holds tokens 2k (low half) and 2k+1
+        const uint32_t lo = (uint32_t)__builtin_amdgcn_sbfe(nm, 2 * k, 1), hi = (uint32_t)__builtin_amdgcn_sbfe(nm, 2 * k + 1, 1);
+        const uint32_t x = d[k] | (lo & 0xFFFFu) | (hi << 16);
+        acc[(2 * k) & 3] = __builtin_fmaxf(acc[(2 * k) & 3], __uint_as_float(x << 16));
+        acc[(2 * k + 1) & 3] = __builtin_fmaxf(acc[(2 * k + 1) & 3], __uint_as_float(x & 0xFFFF0000u));
+    }
+}
+__device__ __forceinline__ void piece_max(const uint4 &v, uint32_t m, uint32_t, float acc[4])
+{
+    const uint32_t d[4] = {v.x, v.y, v.z, v.w};
+    const uint32_t nm = ~m;
+#pragma unroll
+    for (int k = 0; k < 4; k++)
+        acc[k] = __builtin_fmaxf(acc[k], __uint_as_float(d[k] | (uint32_t)__builtin_amdgcn_sbfe(nm, k, 1)));
+}
+
+template <typename Elem, bool kAligned>
+__global__ void __launch_bounds__(256)
+masked_argmax_kernel(const Elem *__restrict__ logits, int64_t row_stride, uint32_t V, uint32_t W,
+                     const uint32_t *__restrict__ bitmask, int32_t *__restrict__ tokens)
+{
+    constexpr uint32_t kPer = 16 / sizeof(Elem);                  // tokens per 16-byte piece: 8 bf16, 4 fp32
+    constexpr uint32_t kSubMask = (1u << kPer) - 1u;
+    constexpr int kPieces = kArgmaxPieces;                        // pieces per thread, all in flight together
+    __shared__ float part_v[4];
+    __shared__ uint32_t part_t[4];
+    const uint32_t b = blockIdx.y, tid = threadIdx.x;
+    const uint32_t *mrow = bitmask + (size_t)b * W;
+    const Elem *row = logits + (int64_t)b * row_stride;
+    const uint32_t n_pieces = (V + kPer - 1u) / kPer;
+    const uint32_t base = blockIdx.x * (kPieces * 256u);
+    // Piece j of thread t is piece base + j*256 + t of the row: the 64 lanes of a wavefront read
+    // 1 KB of consecutive logits with each load.  First every piece's mask bits, then the logits
+    // of the pieces that hold an allowed token, then the arithmetic.
+    uint32_t m[kPieces];
+    union { uint4 v; Elem e[kPer]; } u[kPieces];
+#pragma unroll
+    for (int j = 0; j < kPieces; j++) {
+        const uint32_t p = base + j * 256u + tid;
+        m[j] = p < n_pieces ? (mrow[p * kPer >> 5] >> (p * kPer & 31u)) & kSubMask : 0u;
+    }
+#pragma unroll
+    for (int j = 0; j < kPieces; j++) {
+        const uint32_t p = base + j * 256u + tid;
+        if (kAligned) u[j].v = m[j] ? *reinterpret_cast<const uint4 *>(row + (size_t)p * kPer) : uint4{0u, 0u, 0u, 0u};
+        else {
+#pragma unroll
+            for (uint32_t i = 0; i < kPer; i++)
+                u[j].e[i] = ((m[j] >> i) & 1u) ? row[(size_t)p * kPer + i] : (Elem)0;   // set bits are below V
+        }
+    }
+    // Pass 1, branch-free: the maximum over the thread's allowed tokens as a float.
+    const float nanv = __builtin_nanf("");
+    float acc[4] = {nanv, nanv, nanv, nanv};
+#pragma unroll
+    for (int j = 0; j < kPieces; j++) piece_max(u[j].v, m[j], Elem(0), acc);
+    const float tmax = __builtin_fmaxf(__builtin_fmaxf(acc[0], acc[1]), __builtin_fmaxf(acc[2], acc[3]));
+    float wmax = tmax;                               // workgroup maximum
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) wmax = __builtin_fmaxf(wmax, __shfl_xor(wmax, o));
+    if ((tid & 63u) == 0) part_v[tid >> 6] = wmax;
+    __syncthreads();
+    wmax = __builtin_fmaxf(__builtin_fmaxf(part_v[0], part_v[1]), __builtin_fmaxf(part_v[2], part_v[3]));
+    // Pass 2, only in threads that hold the maximum: the lowest token whose logit equals it
+    // (float equality, so -0.0 and +0.0 tie).  Without any number in this part of the row the
+    // candidate is the lowest allowed token (its logit is a NaN).
+    const bool number = wmax == wmax;
+    uint32_t cand = 0xFFFFFFFFu;
+    if (!number || tmax == wmax) {
+#pragma unroll
+        for (int j = kPieces - 1; j >= 0; j--) {
+            uint32_t eq = 0;
+#pragma unroll
+            for (uint32_t i = 0; i < kPer; i++) eq |= (uint32_t)(elem_float(u[j].e[i]) == wmax) << i;
+            eq = number ? eq & m[j] : m[j];
+            if (eq) cand = (base + j * 256u + tid) * kPer + (uint32_t)__builtin_ctz(eq);
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) { const uint32_t other = __shfl_xor(cand, o); cand = other < cand ? other : cand; }
+    if ((tid & 63u) == 0) part_t[tid >> 6] = cand;
+    __syncthreads();
+    if (tid == 0) {
+        for (uint32_t w = 1; w < 4u; w++) cand = part_t[w] < cand ? part_t[w] : cand;
+        if (cand != 0xFFFFFFFFu) {
+            const uint32_t rank = number ? order_key(__float_as_uint(wmax)) : 0u;
+            atomicMax(&g_argmax_key[b], ((unsigned long long)rank << 32) | (0xFFFFFFFFu - cand));
+        }
+    }
+}
+
+// Turns the merged keys into token ids and leaves the merge area zeroed for the next call.
+__global__ void __launch_bounds__(256)
+masked_argmax_finish_kernel(int32_t *__restrict__ tokens, uint32_t B)
+{
+    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const unsigned long long best = g_argmax_key[b];
+    tokens[b] = best ? (int32_t)(0xFFFFFFFFu - (uint32_t)best) : -1;
+    g_argmax_key[b] = 0ull;
+}
+
 template <typename Elem>
 __global__ void __launch_bounds__(256)
 apply_scalar_kernel(Elem *__restrict__ logits, int64_t row_stride, uint32_t V, uint32_t W,
@@ -669,6 +803,26 @@ hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t
         else
             apply_scalar_kernel<uint16_t><<<g, 256, 0, s>>>((uint16_t *)logits, row_stride, V, W, bitmask, (uint16_t)0xFF80u);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_masked_argmax(const void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
+                                const uint32_t *bitmask, int32_t *tokens, hipStream_t s)
+{
+    uint32_t W = (V + 31u) / 32u;
+    size_t esz = dtype == WG_F32 ? 4 : 2;
+    bool vec_ok = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && ((row_stride * (int64_t)esz) % 16 == 0) &&
+                  (V % 8u == 0);
+    const uint32_t pieces = cdiv(V, dtype == WG_F32 ? 4 : 8);
+    dim3 g(cdiv(pieces, kArgmaxPieces * 256), B);
+    if (dtype == WG_F32) {
+        if (vec_ok) masked_argmax_kernel<uint32_t, true><<<g, 256, 0, s>>>((const uint32_t *)logits, row_stride, V, W, bitmask, tokens);
+        else masked_argmax_kernel<uint32_t, false><<<g, 256, 0, s>>>((const uint32_t *)logits, row_stride, V, W, bitmask, tokens);
+    } else {
+        if (vec_ok) masked_argmax_kernel<uint16_t, true><<<g, 256, 0, s>>>((const uint16_t *)logits, row_stride, V, W, bitmask, tokens);
+        else masked_argmax_kernel<uint16_t, false><<<g, 256, 0, s>>>((const uint16_t *)logits, row_stride, V, W, bitmask, tokens);
+    }
+    masked_argmax_finish_kernel<<<cdiv(B, 256), 256, 0, s>>>(tokens, B);
     return hipGetLastError();
 }
 

@@ -336,6 +336,59 @@ def test_apply_shapes_strides_and_special_values(torch_cuda, dtype, V, stride_pa
         assert (H.host_logit_bits(pad.contiguous()) == 0).all()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V,stride_pad,offset", [(151936, 0, 0), (4104, 8, 0), (1000 + 13, 3, 0), (4096, 0, 1)])
+def test_masked_argmax_matches_oracle(torch_cuda, dtype, V, stride_pad, offset):
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    B, W = 9, (V + 31) // 32
+    x = ws.make_logits(7, B, V, 2.0)
+    x[0, 3], x[0, 4], x[1, 5], x[2, :] = np.nan, np.inf, -0.0, np.nan
+    x[3, 100:200] = 7.5                                   # a long tie
+    m = ws.rng.draw(8, 9, np.arange(B * W)).astype(np.uint32).reshape(B, W)
+    m[:, -1] &= (1 << (V % 32)) - 1 if V % 32 else 0xFFFFFFFF
+    m[4, :] = 0                                           # nothing allowed
+    m[5, :] = 0
+    m[5, W // 2] = 1 << 7                                 # a single allowed token
+    m[6, :] = 0xFFFFFFFF
+    m[6, -1] = m[0, -1] | 1
+    host = x if dtype == "f32" else ws.to_bf16_bits(np.nan_to_num(x, nan=0.0)) | np.where(np.isnan(x), 0x7FC0, 0).astype(np.uint16)
+    want = O.masked_argmax(host, m)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    buf = torch.zeros(B * (V + stride_pad) + offset + 8, dtype=tdt, device="cuda")
+    view = buf[offset:offset + B * (V + stride_pad)].view(B, V + stride_pad)[:, :V]
+    view.copy_(H.dev_logits(host))
+    before = H.host_logit_bits(view.contiguous()).copy()
+    d_tok = torch.full((B,), -7, dtype=torch.int32, device="cuda")
+    wg.masked_argmax(view, torch.from_numpy(m.view(np.int32)).cuda(), d_tok)
+    assert d_tok.cpu().tolist() == want.tolist()
+    assert want[4] == -1 and want[5] == (W // 2) * 32 + 7
+    assert (H.host_logit_bits(view.contiguous()) == before).all()          # logits are only read
+
+
+def test_greedy_decoding_without_writing_logits(torch_cuda):
+    """fill -> masked_argmax -> advance equals fill -> apply -> argmax -> advance (config 1)."""
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    w = ws.make_workload(1)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    cur = H.start_states(o, w)
+    d_states = H.dev_states(cur)
+    d_mask = torch.empty((1, h.W), dtype=torch.int32, device="cuda")
+    d_tok = torch.empty(1, dtype=torch.int32, device="cuda")
+    for k in range(w.steps):
+        h.fill_masks(d_states, d_mask)
+        host = H.logits_for(w, tag=k)
+        wg.masked_argmax(H.dev_logits(host), d_mask, d_tok)
+        masked = O.apply_mask(host.copy(), o.mask_row(tuple(cur[0]))[None, :])
+        tok = int(np.argmax(masked[0]))
+        assert int(d_tok.item()) == tok == int(O.masked_argmax(host, o.mask_row(tuple(cur[0]))[None, :])[0])
+        h.advance(d_states, d_tok)
+        cur = o.advance(cur, [tok])
+        assert (H.host_states(d_states) == cur).all()
+
+
 def test_select_tokens_matches_oracle(torch_cuda):
     torch = torch_cuda
     import paper_2507_16768_amd as wg

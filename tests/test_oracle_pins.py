@@ -337,6 +337,42 @@ def test_apply_matches_numpy_where(dtype):
     assert (again == got).all()                          # idempotent
 
 
+# ---- greedy choice under the mask, against numpy and hand-derived cases ---------------------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_masked_argmax_matches_numpy_on_ordinary_rows(dtype):
+    B, V = 7, 3000 + 5
+    W = (V + 31) // 32
+    x = ws.make_logits(4, B, V, 2.0)
+    m = ws.rng.draw(5, 9, np.arange(B * W)).astype(np.uint32).reshape(B, W)
+    m[:, -1] &= (1 << (V % 32)) - 1
+    bits = np.unpackbits(m.view(np.uint8).reshape(B, -1), axis=1, bitorder="little")[:, :V].astype(bool)
+    if dtype == "bf16":
+        raw = ws.to_bf16_bits(x)
+        val = (raw.astype(np.uint32) << 16).view(np.float32)          # many ties after rounding
+    else:
+        raw, val = x, x
+    want = np.argmax(np.where(bits, val.astype(np.float64), -np.inf), axis=1)   # first maximum
+    assert (O.masked_argmax(raw, m) == want).all()
+
+
+def test_masked_argmax_ties_nan_zero_and_empty_rows():
+    inf, nan = np.inf, np.nan
+    rows = np.array([
+        [1.0, 5.0, 5.0, 2.0, 5.0, 0.0, 0.0, 0.0],      # tie between 1, 2, 4 -> 1
+        [nan, nan, -inf, nan, 0.0, 0.0, 0.0, 0.0],     # -inf beats NaN -> 2 (4.. are masked off below)
+        [nan, nan, nan, nan, 0.0, 0.0, 0.0, 0.0],      # only NaN allowed -> lowest allowed id
+        [-0.0, 0.0, -1.0, -0.0, 9.0, 9.0, 9.0, 9.0],   # -0.0 equals +0.0 -> 0
+        [3.0, 2.0, 1.0, 0.0, 0.0, 0.0, 0.0, 0.0],      # nothing allowed -> -1
+        [1.0, 2.0, 3.0, inf, 4.0, inf, 0.0, nan],      # +inf, first of the two
+    ], dtype=np.float32)
+    mask = np.array([[0b00011111], [0b00001111], [0b00001010], [0b00001111], [0], [0b11111111]], dtype=np.uint32)
+    want = [1, 2, 1, 0, -1, 3]
+    assert O.masked_argmax(rows, mask).tolist() == want
+    assert O.masked_argmax(ws.to_bf16_bits(np.nan_to_num(rows, nan=0.0)) | np.where(np.isnan(rows), 0x7FC0, 0).astype(np.uint16),
+                           mask).tolist() == want
+
+
 # ---- P10: memoised trajectory masks equal fresh walks ---------------------------------------
 
 def test_trajectory_is_consistent_with_unmemoised_calls():
