@@ -488,15 +488,25 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&Cc.ctr->builds, (unsigned long long)n_miss);
 }
 
+// gather: bitmask[b] <- the cached row of request b's key (zeros without a key).  Rows are copied
+// 16 bytes per thread when the caller's row stride allows it.
+template <bool kVec>
 __global__ void __launch_bounds__(256)
 gather_kernel(DeviceCache Cc, uint32_t W, uint32_t *__restrict__ bitmask)
 {
-    uint32_t b = blockIdx.y;
-    uint32_t key = Cc.key_of[b];
+    const uint32_t b = blockIdx.y;
+    const uint32_t key = Cc.key_of[b];
     const uint32_t *src = Cc.arena + (size_t)key * Cc.row_stride;
     uint32_t *dst = bitmask + (size_t)b * W;
-    for (uint32_t w = blockIdx.x * blockDim.x + threadIdx.x; w < W; w += gridDim.x * blockDim.x)
-        dst[w] = key == kNoKey ? 0u : src[w];
+    if (kVec) {
+        const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
+        uint4 *d4 = reinterpret_cast<uint4 *>(dst);
+        for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < W / 4u; q += gridDim.x * blockDim.x)
+            d4[q] = key == kNoKey ? uint4{0u, 0u, 0u, 0u} : s4[q];
+    } else {
+        for (uint32_t w = blockIdx.x * blockDim.x + threadIdx.x; w < W; w += gridDim.x * blockDim.x)
+            dst[w] = key == kNoKey ? 0u : src[w];
+    }
     // the miss lists have been consumed by the kernels that ran before this one
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { Cc.ctr->n_miss = 0; Cc.ctr->n_class_miss = 0; }
 }
@@ -778,8 +788,9 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
     uint32_t kb = n_cu * 2u;
     launch(key_build_kernel, dim3(B < kb ? B : kb), dim3(1024), Cc.row_stride * 4u, s,
            ev ? ev + 4 : nullptr, T, Vc, Cc);
-    launch(gather_kernel, dim3(cdiv(Vc.W, 256 * 4), B), dim3(256), 0, s, ev ? ev + 6 : nullptr, Cc, Vc.W,
-           bitmask);
+    const bool vec = Vc.W % 4u == 0 && reinterpret_cast<uintptr_t>(bitmask) % 16 == 0;
+    if (vec) launch(gather_kernel<true>, dim3(cdiv(Vc.W / 4u, 256), B), dim3(256), 0, s, ev ? ev + 6 : nullptr, Cc, Vc.W, bitmask);
+    else launch(gather_kernel<false>, dim3(cdiv(Vc.W, 256 * 4), B), dim3(256), 0, s, ev ? ev + 6 : nullptr, Cc, Vc.W, bitmask);
     return hipGetLastError();
 }
 
