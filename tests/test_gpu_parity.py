@@ -283,6 +283,50 @@ def test_cache_cold_warm_and_duplicates(torch_cuda):
     assert s3["keys"] >= h.num_states and s3["arena_bytes"] >= s3["keys"] * h.W * 4
 
 
+def test_batch_larger_than_any_before_grows_the_call_scratch(torch_cuda):
+    """The per-call lists start at 1,024 entries; a batch of 2,500 makes the handle grow them."""
+    torch = torch_cuda
+    w = ws.make_workload(5, V=3001, B=2500, steps=3)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    cur = H.start_states(o, w)
+    small = H.dev_states(cur[:100])
+    d_small = torch.empty((100, h.W), dtype=torch.int32, device="cuda")
+    h.fill_masks(small, d_small)                            # first a small call, then the large one
+    toks, sts, _ = o.trajectory(cur, w.token_draws(3))
+    d_states = H.dev_states(cur)
+    d_mask = torch.empty((2500, h.W), dtype=torch.int32, device="cuda")
+    for k in range(3):
+        h.fill_masks(d_states, d_mask)
+        assert (H.host_mask(d_mask) == o.fill_masks(cur)).all(), k
+        h.advance(d_states, torch.from_numpy(toks[k]).cuda())
+        cur = o.advance(cur, toks[k])
+        assert (H.host_states(d_states) == cur).all()
+    assert (H.host_mask(d_small) == o.fill_masks(H.start_states(o, w)[:100])).all()
+
+
+def test_two_handles_share_one_vocabulary(torch_cuda):
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    w2, w3 = ws.make_workload(2, V=4099, B=4, steps=1), ws.make_workload(3, V=4099, B=4, steps=1)
+    assert (w2.vocab.bytes == w3.vocab.bytes).all()
+    gv = wg.Vocab(w2.vocab.bytes, w2.vocab.offsets, w2.vocab.eos_id)
+    h2 = wg.Handle(w2.texts, w2.args, gv)
+    h3 = wg.Handle(w3.texts, w3.args, gv)
+    o2, o3 = H.make_oracle(w2), H.make_oracle(w3)
+    for h, o, w in ((h2, o2, w2), (h3, o3, w3), (h2, o2, w2)):
+        st = H.start_states(o, w)
+        d_mask = torch.empty((4, h.W), dtype=torch.int32, device="cuda")
+        h.fill_masks(H.dev_states(st), d_mask)
+        assert (H.host_mask(d_mask) == o.fill_masks(st)).all()
+    del h2
+    st = H.start_states(o3, w3)
+    d_mask = torch.empty((4, h3.W), dtype=torch.int32, device="cuda")
+    h3.cache_clear()
+    h3.fill_masks(H.dev_states(st), d_mask)
+    assert (H.host_mask(d_mask) == o3.fill_masks(st)).all()
+
+
 def test_error_states_and_illegal_tokens(torch_cuda):
     torch = torch_cuda
     w = ws.make_workload(2, V=5003, B=6, steps=1)

@@ -124,3 +124,11 @@ def test_argument_checks_without_a_gpu():
     assert t.num_states == 1 + 3 + 2 and t.start_state(1) == 4
     with pytest.raises(wg.WgError):
         t.state(99)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout.strip() == ""
