@@ -82,9 +82,12 @@ typedef struct {
     uint64_t lookups;       /* request-steps served by wg_fill_masks */
     uint64_t hits;          /* ... whose mask was already cached */
     uint64_t builds;        /* mask rows built (one per distinct missing key) */
+    uint64_t uncached_builds;/* ... of which could not be kept because every cache row was taken */
     uint64_t class_scans;   /* vocabulary scans (one per distinct missing allow/wait class table) */
     uint64_t entries_walked;/* early-exit tokens examined by the row builds */
-    uint64_t keys;          /* cache keys the handle can hold (fixed at compile) */
+    uint64_t keys;          /* distinct masks the compiled instances can ask for */
+    uint64_t cache_rows;    /* rows the cache can hold (wg_cache_resize) */
+    uint64_t rows_in_use;   /* rows holding a mask since the last clear */
     uint64_t arena_bytes;   /* device bytes reserved for cached rows and class indexes */
 } wg_cache_stats_t;
 
@@ -129,6 +132,11 @@ void wg_vocab_destroy(wg_vocab_t v);
  * lmax is the longest token length the masks will be built for. */
 int wg_lower(const char *const *templates, const wg_args_t *args, uint32_t n_templates,
              uint32_t flags, uint32_t lmax, wg_table_t *out);
+/* appends instances to a table, numbering their states after the existing ones (the host
+ * half of wg_add_instances); on WG_ERR_PARSE the table is unchanged */
+int wg_table_add_instances(wg_table_t t, const char *const *templates, const wg_args_t *args,
+                           uint32_t n_templates);
+uint32_t wg_table_num_instances(wg_table_t t);
 uint32_t wg_table_num_states(wg_table_t t);
 uint32_t wg_table_start_state(wg_table_t t, uint32_t instance);
 int wg_table_state(wg_table_t t, uint32_t sid, wg_state_info_t *out);
@@ -140,6 +148,27 @@ void wg_table_destroy(wg_table_t t);
 int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_templates,
                wg_vocab_t vocab, uint32_t flags, wg_handle_t *out, wg_state_t *start_states_out);
 void wg_destroy(wg_handle_t h);
+
+/* wg_add_instances: instantiate further requests on a live handle (a new request arriving in a
+ * running batch brings its own dynamic arguments; the static structure of a template text seen
+ * before is reused).  State ids, cached rows and class indexes of the existing instances stay
+ * valid; start_states_out[i] (host, may be NULL) receives the start state of new instance i.
+ * The new table slices are copied on `stream`, which is synchronised before the call returns;
+ * when the tables outgrow the room reserved for them (half again of what was needed at the
+ * last growth) the whole device is synchronised once and the tables move.  On WG_ERR_PARSE
+ * nothing was added.  Not to be called while another thread enqueues work on the handle. */
+int wg_add_instances(wg_handle_t h, const char *const *templates, const wg_args_t *args,
+                     uint32_t n_templates, wg_state_t *start_states_out, void *stream);
+uint32_t wg_num_instances(wg_handle_t h);
+
+/* wg_cache_resize: the cache holds `rows` mask rows from now on (one row is 4*ceil(V/128)*4
+ * bytes).  wg_compile sizes it for every key of its instances (at least 4096 rows, at most a
+ * quarter of the free device memory).  Rows are handed out in order of first use; once all are
+ * taken, further keys are still served correctly but rebuilt on every call that needs them
+ * (wg_cache_stats.uncached_builds counts them) until wg_cache_clear or a resize.  Synchronises
+ * the device and clears the cache. */
+int wg_cache_resize(wg_handle_t h, uint32_t rows);
+
 uint32_t wg_num_states(wg_handle_t h);
 uint32_t wg_mask_words(wg_handle_t h);      /* W = ceil(V/32) */
 
@@ -177,7 +206,8 @@ int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uin
 /* Forget every cached mask row and every class-table index built from the operators' allow /
  * wait sets.  O(1) and launches nothing: the handle's cache generation is bumped on the host
  * and travels with every later call as a kernel argument (so a clear recorded into a HIP
- * graph has no effect on replays).  The static indexes of the vocabulary itself (made by
+ * graph has no effect on replays, and a graph holding calls of this handle has to be recorded
+ * again after a clear, a resize or wg_add_instances).  The static indexes of the vocabulary itself (made by
  * wg_vocab_create) are not part of the cache. */
 int wg_cache_clear(wg_handle_t h, void *stream);
 

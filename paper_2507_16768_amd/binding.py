@@ -33,7 +33,8 @@ class _Args(C.Structure):
 
 
 class _Stats(C.Structure):
-    _fields_ = [(k, C.c_uint64) for k in ("lookups", "hits", "builds", "class_scans", "entries_walked", "keys",
+    _fields_ = [(k, C.c_uint64) for k in ("lookups", "hits", "builds", "uncached_builds", "class_scans",
+                                           "entries_walked", "keys", "cache_rows", "rows_in_use",
                                            "arena_bytes")]
 
 
@@ -54,6 +55,8 @@ EXPORTS = [
     "wg_compile", "wg_destroy", "wg_num_states", "wg_mask_words", "wg_fill_masks",
     "wg_apply_mask", "wg_advance", "wg_cache_clear", "wg_cache_stats", "wg_error_count",
     "wg_last_error", "wg_select_tokens", "wg_profile_enable", "wg_profile_read", "wg_masked_argmax",
+    "wg_add_instances", "wg_num_instances", "wg_cache_resize", "wg_table_add_instances",
+    "wg_table_num_instances",
 ]
 
 
@@ -77,6 +80,9 @@ def load_library():
     L.wg_vocab_destroy.argtypes = [vp]
     L.wg_vocab_destroy.restype = None
     L.wg_lower.argtypes = [C.POINTER(C.c_char_p), C.POINTER(_Args), u32, u32, u32, C.POINTER(vp)]
+    L.wg_table_add_instances.argtypes = [vp, C.POINTER(C.c_char_p), C.POINTER(_Args), u32]
+    L.wg_table_num_instances.argtypes = [vp]
+    L.wg_table_num_instances.restype = u32
     L.wg_table_num_states.argtypes = [vp]
     L.wg_table_num_states.restype = u32
     L.wg_table_start_state.argtypes = [vp, u32]
@@ -88,6 +94,10 @@ def load_library():
     L.wg_compile.argtypes = [C.POINTER(C.c_char_p), C.POINTER(_Args), u32, vp, u32, C.POINTER(vp), vp]
     L.wg_destroy.argtypes = [vp]
     L.wg_destroy.restype = None
+    L.wg_add_instances.argtypes = [vp, C.POINTER(C.c_char_p), C.POINTER(_Args), u32, vp, vp]
+    L.wg_num_instances.argtypes = [vp]
+    L.wg_num_instances.restype = u32
+    L.wg_cache_resize.argtypes = [vp, u32]
     L.wg_num_states.argtypes = [vp]
     L.wg_num_states.restype = u32
     L.wg_mask_words.argtypes = [vp]
@@ -163,6 +173,13 @@ class Table:
         self.n_templates = n
         self.num_states = L.wg_table_num_states(self._t)
 
+    def add_instances(self, texts, args=None):
+        L = load_library()
+        c_texts, c_args, n, _keep = _marshal_templates(texts, args)
+        _check(L.wg_table_add_instances(self._t, c_texts, c_args, n))
+        self.n_templates = L.wg_table_num_instances(self._t)
+        self.num_states = L.wg_table_num_states(self._t)
+
     def start_state(self, i=0):
         return load_library().wg_table_start_state(self._t, i)
 
@@ -233,6 +250,22 @@ class Handle:
             raise ValueError("states must be [B, 2] and tokens [B]")
         _check(load_library().wg_advance(self._h, _dev(states, torch.int32, "states"),
                                          _dev(tokens, torch.int32, "tokens"), B, _stream_ptr(stream)))
+
+    def add_instances(self, texts, args, stream=None):
+        """wg_add_instances: returns the start states [n, 2] of the new instances."""
+        L = load_library()
+        c_texts, c_args, n, _keep = _marshal_templates(texts, args)
+        starts = np.zeros((max(n, 1), 2), dtype=np.uint32)
+        _check(L.wg_add_instances(self._h, c_texts, c_args, n, starts.ctypes.data, _stream_ptr(stream)))
+        self.start_states = np.concatenate([self.start_states, starts[:n]])
+        self.num_states = L.wg_num_states(self._h)
+        return starts[:n]
+
+    def num_instances(self):
+        return load_library().wg_num_instances(self._h)
+
+    def cache_resize(self, rows):
+        _check(load_library().wg_cache_resize(self._h, int(rows)))
 
     def cache_clear(self, stream=None):
         _check(load_library().wg_cache_clear(self._h, _stream_ptr(stream)))

@@ -18,7 +18,10 @@ void set_last_error(const std::string &msg) { g_last_error = msg; }
 
 using namespace wg;
 
-struct wg_table_s { Table t; };
+struct wg_table_s {
+    Lowering low;
+    wg_table_s(uint32_t flags, uint32_t lmax) : low(flags, lmax) {}
+};
 
 struct wg_vocab_s {
     DeviceVocab dv{};
@@ -36,19 +39,26 @@ struct wg_vocab_s {
 
 struct wg_handle_s {
     wg_vocab_s *vocab = nullptr;
-    Table table;
+    Lowering low;
     DeviceTable dt{};
     DeviceCache dc{};
+    // device copies of the table, with room to append (capacities in elements)
     StateDesc *d_states = nullptr;
     uint8_t *d_classes = nullptr, *d_lit = nullptr;
+    uint32_t cap_states = 0, cap_classes = 0, cap_keys = 0;
+    uint32_t up_states = 0, up_classes = 0;           // how much of the host table is on the device
+    // class index storage: one buffer of V exit entries per class table in use, and the
+    // device table of their addresses
+    std::vector<ExitEntry *> class_bufs;
+    ExitEntry **d_class_entries = nullptr;
     uint32_t max_batch = 0;
     uint32_t n_cu = 256;
-    uint64_t arena_bytes = 0;
     // kernel timing: events recorded since the last wg_profile_read
     bool profiling = false;
     std::vector<hipEvent_t> fill_events;       // 8 per wg_fill_masks call: begin / end of each kernel
     std::vector<hipEvent_t> advance_events;    // 2 per wg_advance call
     std::vector<hipEvent_t> spare_events;
+    wg_handle_s(uint32_t flags, uint32_t lmax) : low(flags, lmax) {}
 };
 
 namespace {
@@ -86,14 +96,121 @@ int ensure_batch(wg_handle_s *h, uint32_t B) {
     uint32_t nb = h->max_batch ? h->max_batch : 1024;
     while (nb < B) nb *= 2;
     WG_HIP(hipDeviceSynchronize());
-    if (h->dc.key_of) (void)hipFree(h->dc.key_of);
+    if (h->dc.row_ref) (void)hipFree(h->dc.row_ref);
     if (h->dc.miss) (void)hipFree(h->dc.miss);
     if (h->dc.class_miss) (void)hipFree(h->dc.class_miss);
-    h->dc.key_of = nullptr; h->dc.miss = nullptr; h->dc.class_miss = nullptr; h->max_batch = 0;
-    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.key_of), nb * sizeof(uint32_t)));
+    h->dc.row_ref = nullptr; h->dc.miss = nullptr; h->dc.class_miss = nullptr; h->max_batch = 0;
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.row_ref), nb * sizeof(uint32_t)));
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.miss), nb * sizeof(MissEntry)));
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_miss), nb * sizeof(uint32_t)));
     h->max_batch = nb;
+    return WG_OK;
+}
+
+
+// Gives *p room for new_n elements, keeping the first keep_n and zero-filling the rest.
+template <class T> int regrow(T **p, size_t keep_n, size_t new_n, size_t pad_bytes = 0) {
+    T *q = nullptr;
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&q), new_n * sizeof(T) + pad_bytes));
+    hipError_t e = hipMemset(q, 0, new_n * sizeof(T) + pad_bytes);
+    if (e == hipSuccess && keep_n && *p) e = hipMemcpy(q, *p, keep_n * sizeof(T), hipMemcpyDeviceToDevice);
+    if (e != hipSuccess) {
+        (void)hipFree(q);
+        return fail(WG_ERR_HIP, std::string("growing a device table: ") + hipGetErrorString(e));
+    }
+    (void)hipFree(*p);
+    *p = q;
+    return WG_OK;
+}
+
+uint32_t grown(uint32_t need, uint32_t floor_n) {
+    uint64_t n = need < floor_n ? floor_n : need;
+    n += n / 2;                                        // headroom for instances added later
+    return n > 0xFFFFFFF0ull ? 0xFFFFFFF0u : (uint32_t)n;
+}
+
+// Brings the device copy of the table up to date with the host table after instances were
+// appended.  Within the reserved capacities this only copies the new slices (ordered on `s`
+// with the caller's other work); beyond them the device is synchronised once and the tables move.
+int sync_table(wg_handle_s *h, hipStream_t s) {
+    const Table &t = h->low.table;
+    const uint32_t n_states = (uint32_t)t.states.size(), n_classes = (uint32_t)(t.classes.size() / 256);
+    const uint32_t row_stride = h->dc.row_stride, V = h->vocab->dv.V;
+    if (n_states > h->cap_states || n_classes > h->cap_classes || t.n_keys > h->cap_keys)
+        WG_HIP(hipDeviceSynchronize());
+    if (n_states > h->cap_states) {
+        const uint32_t nc = grown(n_states, 4096);
+        int rc = regrow(&h->d_states, h->up_states, nc);
+        // the literal bytes are read 8 at a time: keep 16 zero bytes behind the last state
+        if (rc == WG_OK) rc = regrow(&h->d_lit, h->up_states, nc, 16);
+        if (rc != WG_OK) return rc;
+        h->cap_states = nc;
+    }
+    if (t.n_keys > kMaxKeys) return fail(WG_ERR_NOMEM, "more than 2^31 - 2 cache keys");
+    if (t.n_keys > h->cap_keys) {
+        const uint32_t nc = grown(t.n_keys, 4096);
+        int rc = regrow(&h->dc.tags, h->cap_keys, nc);
+        if (rc != WG_OK) return rc;
+        h->cap_keys = nc;
+    }
+    if (n_classes > h->cap_classes) {
+        const uint32_t nc = grown(n_classes, 64);
+        int rc = regrow(&h->d_classes, (size_t)h->up_classes * 256, (size_t)nc * 256);
+        if (rc == WG_OK) rc = regrow(&h->dc.class_built, h->cap_classes, nc);
+        // one pair of counters per class table, 128 bytes apart so that appends to different
+        // tables do not meet in one cache line
+        if (rc == WG_OK) rc = regrow(&h->dc.class_count, (size_t)h->cap_classes * 32, (size_t)nc * 32);
+        if (rc == WG_OK) rc = regrow(&h->dc.class_rows, (size_t)h->cap_classes * 2 * row_stride, (size_t)nc * 2 * row_stride);
+        if (rc == WG_OK) rc = regrow(&h->d_class_entries, h->cap_classes, nc);
+        if (rc != WG_OK) return rc;
+        h->cap_classes = nc;
+    }
+    if (n_states > h->up_states) {
+        const uint32_t a = h->up_states, n = n_states - a;
+        WG_HIP(hipMemcpyAsync(h->d_states + a, t.states.data() + a, n * sizeof(StateDesc), hipMemcpyHostToDevice, s));
+        WG_HIP(hipMemcpyAsync(h->d_lit + a, t.lit.data() + a, n, hipMemcpyHostToDevice, s));
+        // the copies read pageable host memory that a later append may move
+        WG_HIP(hipStreamSynchronize(s));
+        h->up_states = n_states;
+    }
+    if (n_classes > h->up_classes) {
+        const uint32_t a = h->up_classes, n = n_classes - a;
+        WG_HIP(hipMemcpyAsync(h->d_classes + (size_t)a * 256, t.classes.data() + (size_t)a * 256, (size_t)n * 256,
+                              hipMemcpyHostToDevice, s));
+        for (uint32_t c = a; c < n_classes; c++) {
+            ExitEntry *buf = nullptr;
+            WG_HIP(hipMalloc(reinterpret_cast<void **>(&buf), (size_t)V * sizeof(ExitEntry)));
+            h->class_bufs.push_back(buf);
+        }
+        WG_HIP(hipMemcpyAsync(h->d_class_entries + a, h->class_bufs.data() + a, n * sizeof(ExitEntry *),
+                              hipMemcpyHostToDevice, s));
+        WG_HIP(hipStreamSynchronize(s));
+        h->up_classes = n_classes;
+    }
+    h->dt = DeviceTable{h->d_states, h->d_classes, h->d_lit, n_states, t.lmax, n_classes};
+    h->dc.class_entries = h->d_class_entries;
+    h->dc.n_keys = t.n_keys;
+    return WG_OK;
+}
+
+int set_cache_rows(wg_handle_s *h, uint32_t rows) {
+    const size_t row_bytes = (size_t)h->dc.row_stride * 4u;
+    uint32_t *arena = nullptr;
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&arena), (size_t)rows * row_bytes + 16));
+    (void)hipFree(h->dc.arena);
+    h->dc.arena = arena;
+    h->dc.cap_rows = rows;
+    return WG_OK;
+}
+
+// A new cache generation: every row and class index made so far is stale from the next call on.
+int next_generation(wg_handle_s *h, hipStream_t s) {
+    if (++h->dc.epoch >= (1u << 30)) {                 // out of generation numbers: reset the tags for real
+        WG_HIP(hipMemsetAsync(h->dc.tags, 0, (size_t)h->cap_keys * sizeof(unsigned long long), s));
+        WG_HIP(hipMemsetAsync(h->dc.class_built, 0, (size_t)h->cap_classes * sizeof(uint32_t), s));
+        WG_HIP(hipMemsetAsync(&h->dc.ctr->slot_ctr, 0, sizeof(unsigned long long), s));
+        h->dc.epoch = 1;
+    }
     return WG_OK;
 }
 
@@ -201,8 +318,8 @@ int wg_lower(const char *const *templates, const wg_args_t *args, uint32_t n_tem
     if (!templates || n_templates == 0) return fail(WG_ERR_INVALID, "wg_lower: no templates");
     if (flags & ~(uint32_t)WG_EOS_RESTART) return fail(WG_ERR_INVALID, "wg_lower: unknown flag bits");
     try {
-        std::unique_ptr<wg_table_s> t(new wg_table_s);
-        lower(templates, args, n_templates, flags, lmax, t->t);
+        std::unique_ptr<wg_table_s> t(new wg_table_s(flags, lmax));
+        t->low.add(templates, args, n_templates);
         *out = t.release();
         return WG_OK;
     } catch (const std::bad_alloc &) {
@@ -212,28 +329,45 @@ int wg_lower(const char *const *templates, const wg_args_t *args, uint32_t n_tem
     }
 }
 
-uint32_t wg_table_num_states(wg_table_t t) { return t ? (uint32_t)t->t.states.size() : 0; }
+int wg_table_add_instances(wg_table_t t, const char *const *templates, const wg_args_t *args,
+                           uint32_t n_templates) {
+    if (!t) return fail(WG_ERR_INVALID, "wg_table_add_instances: null table");
+    if (!templates || n_templates == 0) return fail(WG_ERR_INVALID, "wg_table_add_instances: no templates");
+    try {
+        t->low.add(templates, args, n_templates);
+        return WG_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(WG_ERR_NOMEM, "wg_table_add_instances: out of host memory");
+    } catch (const std::exception &e) {
+        return fail(WG_ERR_PARSE, e.what());
+    }
+}
+
+uint32_t wg_table_num_instances(wg_table_t t) { return t ? (uint32_t)t->low.table.start.size() : 0; }
+
+uint32_t wg_table_num_states(wg_table_t t) { return t ? (uint32_t)t->low.table.states.size() : 0; }
 
 uint32_t wg_table_start_state(wg_table_t t, uint32_t i) {
-    return (t && i < t->t.start.size()) ? t->t.start[i] : WG_SID_ERROR;
+    return (t && i < t->low.table.start.size()) ? t->low.table.start[i] : WG_SID_ERROR;
 }
 
 int wg_table_state(wg_table_t t, uint32_t sid, wg_state_info_t *out) {
-    if (!t || !out || sid >= t->t.states.size()) return fail(WG_ERR_INVALID, "wg_table_state: bad argument");
-    const StateDesc &d = t->t.states[sid];
+    if (!t || !out || sid >= t->low.table.states.size()) return fail(WG_ERR_INVALID, "wg_table_state: bad argument");
+    const Table &tb = t->low.table;
+    const StateDesc &d = tb.states[sid];
     out->kind = d.kind_byte & 0xFFu; out->byte = (d.kind_byte >> 8) & 0xFFu;
     out->next_a = d.next_a; out->next_b = d.next_b; out->eos_next = d.eos_next; out->max = d.max;
-    out->tmpl = t->t.tmpl[sid]; out->n_keys = t->t.key_count[sid];
+    out->tmpl = tb.tmpl[sid]; out->n_keys = tb.key_count[sid];
     return WG_OK;
 }
 
 int wg_table_symbol_class(wg_table_t t, uint32_t sid, uint32_t symbol) {
-    if (!t || sid >= t->t.states.size() || symbol > kSymEos) return fail(WG_ERR_INVALID, "wg_table_symbol_class: bad argument");
-    const StateDesc &d = t->t.states[sid];
+    if (!t || sid >= t->low.table.states.size() || symbol > kSymEos) return fail(WG_ERR_INVALID, "wg_table_symbol_class: bad argument");
+    const StateDesc &d = t->low.table.states[sid];
     uint32_t kind = d.kind_byte & 0xFFu;
     if (symbol == kSymEos) return d.eos_next == WG_SID_ERROR ? CLS_REJECT : CLS_EXIT_A;
     if (kind == WG_KIND_LIT) return symbol == ((d.kind_byte >> 8) & 0xFFu) ? CLS_EXIT_A : CLS_REJECT;
-    if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) return t->t.classes[(size_t)d.cls * 256 + symbol];
+    if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) return t->low.table.classes[(size_t)d.cls * 256 + symbol];
     return CLS_REJECT;
 }
 
@@ -243,11 +377,13 @@ void wg_table_destroy(wg_table_t t) { delete t; }
 
 void wg_destroy(wg_handle_t h) {
     if (!h) return;
+    (void)hipDeviceSynchronize();
     (void)hipFree(h->d_states); (void)hipFree(h->d_classes); (void)hipFree(h->d_lit);
-    (void)hipFree(h->dc.ctr); (void)hipFree(h->dc.built); (void)hipFree(h->dc.arena);
-    (void)hipFree(h->dc.key_of); (void)hipFree(h->dc.miss); (void)hipFree(h->dc.class_miss);
+    (void)hipFree(h->dc.ctr); (void)hipFree(h->dc.tags); (void)hipFree(h->dc.arena);
+    (void)hipFree(h->dc.row_ref); (void)hipFree(h->dc.miss); (void)hipFree(h->dc.class_miss);
     (void)hipFree(h->dc.class_built); (void)hipFree(h->dc.class_rows);
-    (void)hipFree(h->dc.class_entries); (void)hipFree(h->dc.class_count);
+    (void)hipFree(h->d_class_entries); (void)hipFree(h->dc.class_count);
+    for (ExitEntry *b : h->class_bufs) (void)hipFree(b);
     for (auto *v : {&h->fill_events, &h->advance_events, &h->spare_events})
         for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
     delete h;
@@ -260,60 +396,51 @@ int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_t
     if (!vocab) return fail(WG_ERR_INVALID, "wg_compile: vocab is null");
     if (!templates || n_templates == 0) return fail(WG_ERR_INVALID, "wg_compile: no templates");
     if (flags & ~(uint32_t)WG_EOS_RESTART) return fail(WG_ERR_INVALID, "wg_compile: unknown flag bits");
-    std::unique_ptr<wg_handle_s, void (*)(wg_handle_t)> h(new (std::nothrow) wg_handle_s, wg_destroy);
+    std::unique_ptr<wg_handle_s, void (*)(wg_handle_t)> h(
+        new (std::nothrow) wg_handle_s(flags, vocab->dv.lmax), wg_destroy);
     if (!h) return fail(WG_ERR_NOMEM, "wg_compile: out of host memory");
     try {
-        lower(templates, args, n_templates, flags, vocab->dv.lmax, h->table);
+        h->low.add(templates, args, n_templates);
     } catch (const std::bad_alloc &) {
         return fail(WG_ERR_NOMEM, "wg_compile: out of host memory");
     } catch (const std::exception &e) {
         return fail(WG_ERR_PARSE, e.what());
     }
     h->vocab = vocab;
-    const Table &t = h->table;
+    const Table &t = h->low.table;
     WG_HIP(hipSetDevice(vocab->device));
     hipDeviceProp_t prop;
     WG_HIP(hipGetDeviceProperties(&prop, vocab->device));
     h->n_cu = prop.multiProcessorCount > 0 ? (uint32_t)prop.multiProcessorCount : 256u;
 
     const uint32_t row_stride = vocab->dv.row_stride;
-    const uint32_t n_classes = (uint32_t)(t.classes.size() / 256);
-    if ((uint64_t)row_stride * 4ull > 160ull * 1024ull)
+    const uint64_t row_bytes = (uint64_t)row_stride * 4ull;
+    if (row_bytes > 160ull * 1024ull)
         return fail(WG_ERR_INVALID, "wg_compile: a mask row does not fit the 160 KB of LDS (vocabulary too large)");
     WG_HIP(configure_kernels(row_stride * 4u));
-    // the class index: 2 rows and up to V exit entries per class table
-    const uint64_t class_bytes = (uint64_t)n_classes * (2ull * row_stride * 4ull + (uint64_t)vocab->dv.V * sizeof(ExitEntry));
-    uint64_t arena_bytes = (uint64_t)t.n_keys * row_stride * 4ull + class_bytes;
+    h->dc.row_stride = row_stride;
+    h->dc.epoch = 1;                                   // tags start at 0 = never built
+
+    // The row cache: room for every key of the instances given here (at least 4096 rows), but
+    // no more than a quarter of the free device memory; keys beyond it are served uncached.
     size_t free_b = 0, total_b = 0;
     WG_HIP(hipMemGetInfo(&free_b, &total_b));
-    if (arena_bytes > (uint64_t)free_b / 2)
-        return fail(WG_ERR_NOMEM, "wg_compile: the mask cache (" + std::to_string(arena_bytes >> 20) +
-                                      " MiB for " + std::to_string(t.n_keys) +
-                                      " keys) exceeds half of the free device memory");
-    WG_HIP(upload(&h->d_states, t.states.data(), t.states.size()));
-    WG_HIP(upload(&h->d_classes, t.classes.data(), t.classes.size()));
-    WG_HIP(upload(&h->d_lit, t.lit.data(), t.lit.size()));
-    h->dt = DeviceTable{h->d_states, h->d_classes, h->d_lit, (uint32_t)t.states.size(), t.lmax, n_classes};
+    const uint64_t n_classes = t.classes.size() / 256;
+    const uint64_t class_bytes = n_classes * (2ull * row_bytes + (uint64_t)vocab->dv.V * sizeof(ExitEntry));
+    if (class_bytes > (uint64_t)free_b / 4)
+        return fail(WG_ERR_NOMEM, "wg_compile: the class indexes (" + std::to_string(class_bytes >> 20) +
+                                      " MiB for " + std::to_string(n_classes) +
+                                      " allow / wait set tables) exceed a quarter of the free device memory");
+    uint64_t rows = t.n_keys < 4096u ? 4096u : t.n_keys;
+    const uint64_t fit = (uint64_t)free_b / 4 / row_bytes;
+    if (rows > fit) rows = fit ? fit : 1;
+    if (rows > kMaxRows) rows = kMaxRows;
 
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.ctr), sizeof(Counters)));
-    Counters init{};
-    WG_HIP(hipMemcpy(h->dc.ctr, &init, sizeof init, hipMemcpyHostToDevice));
-    h->dc.epoch = 1;                                   // tags start at 0 = never built
-    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.built), (size_t)t.n_keys * sizeof(uint32_t)));
-    WG_HIP(hipMemset(h->dc.built, 0, (size_t)t.n_keys * sizeof(uint32_t)));
-    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.arena), (size_t)t.n_keys * row_stride * 4ull + 16));
-    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_built), n_classes * sizeof(uint32_t)));
-    WG_HIP(hipMemset(h->dc.class_built, 0, n_classes * sizeof(uint32_t)));
-    // one counter per class table, 128 bytes apart so that appends to different tables do not
-    // meet in one cache line
-    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_count), n_classes * 32 * sizeof(uint32_t)));
-    WG_HIP(hipMemset(h->dc.class_count, 0, n_classes * 32 * sizeof(uint32_t)));
-    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_rows), (size_t)n_classes * 2ull * row_stride * 4ull));
-    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_entries), (size_t)n_classes * vocab->dv.V * sizeof(ExitEntry)));
-    h->arena_bytes = arena_bytes;
-    h->dc.row_stride = row_stride;
-    h->dc.n_keys = t.n_keys;
-    int rc = ensure_batch(h.get(), 1024);
+    WG_HIP(hipMemset(h->dc.ctr, 0, sizeof(Counters)));
+    int rc = set_cache_rows(h.get(), (uint32_t)rows);
+    if (rc == WG_OK) rc = sync_table(h.get(), nullptr);
+    if (rc == WG_OK) rc = ensure_batch(h.get(), 1024);
     if (rc != WG_OK) return rc;
     WG_HIP(hipDeviceSynchronize());
     if (start_states_out)
@@ -322,6 +449,38 @@ int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_t
     return WG_OK;
 }
 
+int wg_add_instances(wg_handle_t h, const char *const *templates, const wg_args_t *args,
+                     uint32_t n_templates, wg_state_t *start_states_out, void *stream) {
+    if (!h) return fail(WG_ERR_INVALID, "wg_add_instances: null handle");
+    if (!templates || n_templates == 0) return fail(WG_ERR_INVALID, "wg_add_instances: no templates");
+    const size_t first = h->low.table.start.size();
+    try {
+        h->low.add(templates, args, n_templates);
+    } catch (const std::bad_alloc &) {
+        return fail(WG_ERR_NOMEM, "wg_add_instances: out of host memory");
+    } catch (const std::exception &e) {
+        return fail(WG_ERR_PARSE, e.what());
+    }
+    WG_HIP(hipSetDevice(h->vocab->device));
+    int rc = sync_table(h, static_cast<hipStream_t>(stream));
+    if (rc != WG_OK) return rc;
+    if (start_states_out)
+        for (uint32_t i = 0; i < n_templates; i++)
+            start_states_out[i] = wg_state_t{h->low.table.start[first + i], 0u};
+    return WG_OK;
+}
+
+int wg_cache_resize(wg_handle_t h, uint32_t rows) {
+    if (!h) return fail(WG_ERR_INVALID, "wg_cache_resize: null handle");
+    if (rows == 0 || rows > kMaxRows) return fail(WG_ERR_INVALID, "wg_cache_resize: rows must be 1 .. 2^30");
+    WG_HIP(hipSetDevice(h->vocab->device));
+    WG_HIP(hipDeviceSynchronize());
+    int rc = set_cache_rows(h, rows);
+    if (rc != WG_OK) return rc;
+    return next_generation(h, nullptr);
+}
+
+uint32_t wg_num_instances(wg_handle_t h) { return h ? (uint32_t)h->low.table.start.size() : 0; }
 uint32_t wg_num_states(wg_handle_t h) { return h ? h->dt.n_states : 0; }
 uint32_t wg_mask_words(wg_handle_t h) { return h ? h->vocab->dv.W : 0; }
 
@@ -331,9 +490,9 @@ int wg_fill_masks(wg_handle_t h, const wg_state_t *d_states, uint32_t B, uint32_
                   void *stream) {
     if (!h || !d_states || !d_bitmask) return fail(WG_ERR_INVALID, "wg_fill_masks: null argument");
     if (B == 0) return fail(WG_ERR_INVALID, "wg_fill_masks: B is 0");
+    if (B > kMaxBatch) return fail(WG_ERR_INVALID, "wg_fill_masks: B above 65535");
     int rc = ensure_batch(h, B);
     if (rc != WG_OK) return rc;
-    if (B > 65535u) return fail(WG_ERR_INVALID, "wg_fill_masks: B above 65535");
     hipEvent_t ev[8];
     if (h->profiling) for (auto &e : ev) { e = take_event(h); h->fill_events.push_back(e); }
     WG_HIP(launch_fill(h->dt, h->vocab->dv, h->dc, d_states, B, d_bitmask, h->n_cu,
@@ -347,7 +506,7 @@ int wg_apply_mask(void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V, int6
     if (B == 0 || V == 0) return fail(WG_ERR_INVALID, "wg_apply_mask: empty batch or vocabulary");
     if (dtype != WG_F32 && dtype != WG_BF16) return fail(WG_ERR_INVALID, "wg_apply_mask: unknown dtype");
     if (row_stride_elems < (int64_t)V) return fail(WG_ERR_INVALID, "wg_apply_mask: row stride smaller than V");
-    if (B > 65535u) return fail(WG_ERR_INVALID, "wg_apply_mask: B above 65535");
+    if (B > kMaxBatch) return fail(WG_ERR_INVALID, "wg_apply_mask: B above 65535");
     WG_HIP(launch_apply(d_logits, dtype, B, V, row_stride_elems, d_bitmask, static_cast<hipStream_t>(stream)));
     return WG_OK;
 }
@@ -358,7 +517,7 @@ int wg_masked_argmax(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_
     if (B == 0 || V == 0) return fail(WG_ERR_INVALID, "wg_masked_argmax: empty batch or vocabulary");
     if (dtype != WG_F32 && dtype != WG_BF16) return fail(WG_ERR_INVALID, "wg_masked_argmax: unknown dtype");
     if (row_stride_elems < (int64_t)V) return fail(WG_ERR_INVALID, "wg_masked_argmax: row stride smaller than V");
-    if (B > 65535u) return fail(WG_ERR_INVALID, "wg_masked_argmax: B above 65535");
+    if (B > kMaxBatch) return fail(WG_ERR_INVALID, "wg_masked_argmax: B above 65535");
     WG_HIP(launch_masked_argmax(d_logits, dtype, B, V, row_stride_elems, d_bitmask, d_tokens,
                                 static_cast<hipStream_t>(stream)));
     return WG_OK;
@@ -378,13 +537,7 @@ int wg_cache_clear(wg_handle_t h, void *stream) {
     if (!h) return fail(WG_ERR_INVALID, "wg_cache_clear: null handle");
     // The generation number travels with every later launch as a kernel argument, so the
     // clear is ordered with the caller's other calls on this handle without touching the GPU.
-    if (++h->dc.epoch == 0) {                          // wrapped: reset the tags for real
-        hipStream_t s = static_cast<hipStream_t>(stream);
-        WG_HIP(hipMemsetAsync(h->dc.built, 0, (size_t)h->dc.n_keys * sizeof(uint32_t), s));
-        WG_HIP(hipMemsetAsync(h->dc.class_built, 0, (size_t)h->dt.n_classes * sizeof(uint32_t), s));
-        h->dc.epoch = 1;
-    }
-    return WG_OK;
+    return next_generation(h, static_cast<hipStream_t>(stream));
 }
 
 int wg_cache_stats(wg_handle_t h, wg_cache_stats_t *host_out) {
@@ -393,8 +546,16 @@ int wg_cache_stats(wg_handle_t h, wg_cache_stats_t *host_out) {
     WG_HIP(hipDeviceSynchronize());
     WG_HIP(hipMemcpy(&c, h->dc.ctr, sizeof c, hipMemcpyDeviceToHost));
     host_out->lookups = c.lookups; host_out->hits = c.hits; host_out->builds = c.builds;
+    host_out->uncached_builds = c.uncached_builds;
     host_out->class_scans = c.class_scans; host_out->entries_walked = c.entries_walked;
-    host_out->keys = h->dc.n_keys; host_out->arena_bytes = h->arena_bytes;
+    host_out->keys = h->dc.n_keys;
+    host_out->cache_rows = h->dc.cap_rows;
+    const uint64_t taken = (uint32_t)(c.slot_ctr >> 32) == h->dc.epoch ? (uint32_t)c.slot_ctr : 0u;
+    host_out->rows_in_use = taken < h->dc.cap_rows ? taken : h->dc.cap_rows;
+    const uint64_t row_bytes = (uint64_t)h->dc.row_stride * 4ull;
+    host_out->arena_bytes = (uint64_t)h->dc.cap_rows * row_bytes +
+                            (uint64_t)h->class_bufs.size() * ((uint64_t)h->vocab->dv.V * sizeof(ExitEntry)) +
+                            (uint64_t)h->cap_classes * 2ull * row_bytes;
     return WG_OK;
 }
 

@@ -52,34 +52,58 @@ struct MissEntry {
     uint32_t r;                  // allow-bytes that may still be consumed, capped at lmax
     uint32_t cls;                // WAIT / COND: class table id
     uint32_t ent_lo, ent_cnt;    // LIT: its first-byte bucket in the vocabulary's entry list
-    uint32_t eos_next, next_a, next_b, pad;
+    uint32_t eos_next, next_a, next_b;
+    uint32_t slot;               // arena row of the result, or kNoSlot: build into the bitmask row of `req`
+    uint32_t req;                // the request that claimed the key
+    uint32_t pad[3];
     HopState hop[2];             // successors reached through exit A / exit B
 };
-static_assert(sizeof(MissEntry) == 96, "miss entry layout");
+static_assert(sizeof(MissEntry) == 112, "miss entry layout");
 
 struct Counters {
     uint32_t n_miss;             // state keys to build in the call in flight
     uint32_t n_class_miss;       // class tables to scan in the call in flight
-    unsigned long long lookups, hits, builds, class_scans, entries_walked, errors;
+    unsigned long long slot_ctr; // generation << 32 | arena rows in use in that generation (<= cap_rows)
+    unsigned long long launch;   // number of the fill call in flight (its gather counts it up)
+    unsigned long long lookups, hits, builds, uncached_builds, class_scans, entries_walked, errors;
 };
+
+// A key's 64-bit tag, by its top bit:
+//   0: generation (30 bits) << 32 | arena row.  The row is valid if the generation is the
+//      handle's current cache generation (1 .. 2^30-1); 0 means never built.
+//   1: claimed - 1 << 63 | launch (46 bits) << 16 | request index (16 bits): request `index` of
+//      the fill call `launch` builds the row.  key_build replaces the claim by the row's tag
+//      once the row is in the arena; if the arena was full the claim stays: the row was built
+//      straight into the bitmask row of the claiming request and is not kept, so the key is
+//      missing again in the next call.
+constexpr unsigned long long kTagClaim = 1ull << 63;
+constexpr unsigned long long kTagLaunchMask = (1ull << 46) - 1ull;
+constexpr uint32_t kNoSlot = 0xFFFFFFFFu;
+// What lookup leaves per request for gather: the arena row of a mask cached before the call, or
+// kRefByKey | key for a mask built in this call (its tag then says where it went), or kNoKey
+// (no such state: a row of zeros).  Rows and keys stay below 2^30 and 2^31 - 1.
+constexpr uint32_t kRefByKey = 0x80000000u;
+constexpr uint32_t kMaxRows = 1u << 30, kMaxKeys = 0x7FFFFFFEu;
+constexpr uint32_t kMaxBatch = 65535u;     // request indexes fit the 16 bits of a tag (and grid.y)
 
 struct DeviceCache {
     Counters *ctr;
     // per state key
-    uint32_t *built;             // epoch in which the key's row was built
-    uint32_t *arena;             // n_keys rows of row_stride words
+    unsigned long long *tags;
+    uint32_t *arena;             // cap_rows rows of row_stride words, handed out on demand
+    uint32_t cap_rows;
     // per class table (the context-free part of every mask of a state using that table)
-    uint32_t *class_built;       // epoch in which the class index was built
+    uint32_t *class_built;       // generation in which the class index was built
     uint32_t *class_rows;        // 2 rows per class: [stay] all bytes stay, [end] exits on its last byte
-    ExitEntry *class_entries;    // V entries reserved per class
-    uint32_t *class_count;       // entries in use per class
+    ExitEntry *const *class_entries;   // per class: V entries, filled from both ends
+    uint32_t *class_count;       // entries in use per class (front, back), 128 bytes apart
     // per call
-    uint32_t *key_of;            // [B]
+    uint32_t *row_ref;           // [B] arena row of the request's mask, kRefByKey | key, or kNoKey
     MissEntry *miss;             // [B]
     uint32_t *class_miss;        // [B]
     uint32_t row_stride;         // words, multiple of 4
     uint32_t n_keys;
-    uint32_t epoch;              // cache generation of this call; tag == epoch <=> entry valid
+    uint32_t epoch;              // cache generation of this call
 };
 
 // ev, when not null, holds eight events: a begin / end pair for each of the four kernels of a fill.

@@ -31,7 +31,7 @@ static_assert(sizeof(StateDesc) == 32, "descriptor layout");
 struct Table {
     std::vector<StateDesc> states;        // index = sid; [0] is FINAL
     std::vector<uint8_t> classes;         // n_class_tables * 256
-    std::vector<uint8_t> lit;             // lit[sid] = byte of a LIT state (else 0), padded by 16
+    std::vector<uint8_t> lit;             // lit[sid] = byte of a LIT state (else 0)
     std::vector<uint32_t> tmpl;           // template instance of each state
     std::vector<uint32_t> start;          // start state of each instance
     std::vector<uint32_t> key_count;      // masks per state (1, or lmax+1 for a bounded Wait)
@@ -40,9 +40,23 @@ struct Table {
     uint32_t flags = 0;
 };
 
-// Throws std::runtime_error with a message naming the template and the offset.
-void lower(const char *const *templates, const wg_args_t *args, uint32_t n, uint32_t flags,
-           uint32_t lmax, Table &out);
+// The host operator compiler with its memory: parsed template texts (the static structures)
+// and the class tables seen so far, so that instances can be added to a live table.
+struct LoweringState;
+class Lowering {
+  public:
+    Lowering(uint32_t flags, uint32_t lmax);
+    ~Lowering();
+    Lowering(const Lowering &) = delete;
+    Lowering &operator=(const Lowering &) = delete;
+    // Appends n template instances.  Throws std::runtime_error with a message naming the
+    // template and the offset; the table is then as it was before the call.
+    void add(const char *const *templates, const wg_args_t *args, uint32_t n);
+    Table table;
+
+  private:
+    LoweringState *st_;
+};
 
 void set_last_error(const std::string &msg);
 

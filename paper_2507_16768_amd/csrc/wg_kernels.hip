@@ -132,64 +132,90 @@ __device__ __forceinline__ bool walk_chunks(const DeviceTable &T, uint32_t &sid,
 
 // ---------------------------------------------------------------------------------------------
 // lookup: state -> cache key.  A missing key is claimed by exactly one request (CAS on the
-// key's epoch tag) and queued for key_build; if the key's state is a checkpoint whose class
-// table has no index yet in this epoch, the table is claimed and queued for class_scan.
+// key's tag), gets a row of the arena (or, when the arena is full, is built straight into
+// the claimer's bitmask row and not kept) and is queued for key_build: the i-th claim of a call
+// takes the i-th free row, so the claims' position in the miss list is their row allocation and
+// the count of rows in use is brought up to date once per call, by gather; if the key's state is a
+// checkpoint whose class table has no index yet in this generation, the table is claimed and
+// queued for class_scan.
+
 __global__ void __launch_bounds__(64)
 lookup_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, const wg_state_t *__restrict__ states, uint32_t B)
 {
-    uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
-    bool live = b < B, hit = false;
+    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x, lane = threadIdx.x & 63u;
+    const bool live = b < B;
+    bool hit = false, claimed = false;
+    uint32_t sid = 0, aux = 0, key = kNoKey, kind = 0, variant = 0;
+    const uint32_t epoch = Cc.epoch;
+    const unsigned long long launch = Cc.ctr->launch & kTagLaunchMask;
+    const unsigned long long sc = Cc.ctr->slot_ctr;
+    const uint32_t rows0 = (uint32_t)(sc >> 32) == epoch ? (uint32_t)sc : 0u;   // rows in use before this call
+    uint32_t ref = kNoKey;
+    StateDesc d{};
     if (live) {
-        uint32_t sid = states[b].sid, aux = states[b].aux;
-        uint32_t key = kNoKey;
+        sid = states[b].sid; aux = states[b].aux;
         if (sid < T.n_states) {
-            const StateDesc &d = T.states[sid];
-            uint32_t kind = d.kind_byte & 0xFFu, variant = 0;
+            d = T.states[sid];
+            kind = d.kind_byte & 0xFFu;
             if (kind == WG_KIND_WAIT && d.max != WG_UNBOUNDED) {
-                uint32_t left = d.max > aux ? d.max - aux : 0u;
+                const uint32_t left = d.max > aux ? d.max - aux : 0u;
                 variant = T.lmax - (left < T.lmax ? left : T.lmax);
             }
             key = d.key_base + variant;
-            const uint32_t epoch = Cc.epoch;
-            uint32_t old = __hip_atomic_load(&Cc.built[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            hit = old == epoch;
-            if (!hit && atomicCAS(&Cc.built[key], old, epoch) == old) {
-                // this request builds the key: resolve what key_build needs into the miss entry
-                MissEntry me{};
-                me.key = key; me.sid = sid; me.aux = aux; me.kind = kind;
-                me.r = T.lmax - variant; me.cls = d.cls; me.eos_next = d.eos_next;
-                me.next_a = d.next_a; me.next_b = d.next_b;
-                if (kind == WG_KIND_LIT) {
-                    const uint32_t y = (d.kind_byte >> 8) & 0xFFu;
-                    me.ent_lo = Vc.lit_start[y];
-                    me.ent_cnt = Vc.lit_start[y + 1u] - me.ent_lo;
-                }
+            const unsigned long long t = __hip_atomic_load(&Cc.tags[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // anything but a row of this generation or a claim made in this very call is stale
+            hit = (uint32_t)(t >> 32) == epoch;
+            const bool this_call = t >= kTagClaim && ((t >> 16) & kTagLaunchMask) == launch;
+            if (!hit && !this_call)
+                claimed = atomicCAS(&Cc.tags[key], t, kTagClaim | (launch << 16) | b) == t;
+            ref = hit ? (uint32_t)t : kRefByKey | key;
+        }
+        Cc.row_ref[b] = ref;
+    }
+    // the claimers of a wavefront take their places in the miss list together
+    const unsigned long long cm = __ballot(claimed);
+    if (cm) {
+        uint32_t first = 0;
+        if (lane == (uint32_t)__builtin_ctzll(cm)) first = atomicAdd(&Cc.ctr->n_miss, (uint32_t)__popcll(cm));
+        first = __shfl(first, __builtin_ctzll(cm));
+        if (claimed) {
+            const uint32_t idx = first + (uint32_t)__popcll(cm & ((1ull << lane) - 1ull));
+            const uint32_t slot = Cc.cap_rows - rows0 > idx ? rows0 + idx : kNoSlot;
+            // this request builds the key: resolve what key_build needs into the miss entry
+            MissEntry me{};
+            me.key = key; me.sid = sid; me.aux = aux; me.kind = kind;
+            me.r = T.lmax - variant; me.cls = d.cls; me.eos_next = d.eos_next;
+            me.next_a = d.next_a; me.next_b = d.next_b;
+            me.slot = slot; me.req = b;
+            if (kind == WG_KIND_LIT) {
+                const uint32_t y = (d.kind_byte >> 8) & 0xFFu;
+                me.ent_lo = Vc.lit_start[y];
+                me.ent_cnt = Vc.lit_start[y + 1u] - me.ent_lo;
+            }
 #pragma unroll
-                for (int w = 0; w < 2; w++) {
-                    const uint32_t t = w ? d.next_b : d.next_a;
-                    me.hop[w] = HopState{0xFFu, 0u, WG_SID_ERROR, WG_SID_ERROR, WG_UNBOUNDED, 0u};
-                    if (t < T.n_states) {
-                        const StateDesc &td = T.states[t];
-                        me.hop[w] = HopState{td.kind_byte & 0xFFu, (td.kind_byte >> 8) & 0xFFu,
-                                             td.next_a, td.next_b, td.max, td.cls};
-                    }
+            for (int w = 0; w < 2; w++) {
+                const uint32_t t = w ? d.next_b : d.next_a;
+                me.hop[w] = HopState{0xFFu, 0u, WG_SID_ERROR, WG_SID_ERROR, WG_UNBOUNDED, 0u};
+                if (t < T.n_states) {
+                    const StateDesc &td = T.states[t];
+                    me.hop[w] = HopState{td.kind_byte & 0xFFu, (td.kind_byte >> 8) & 0xFFu,
+                                         td.next_a, td.next_b, td.max, td.cls};
                 }
-                Cc.miss[atomicAdd(&Cc.ctr->n_miss, 1u)] = me;
-                if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
-                    uint32_t c = d.cls;
-                    uint32_t oc = __hip_atomic_load(&Cc.class_built[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    if (oc != epoch && atomicCAS(&Cc.class_built[c], oc, epoch) == oc) {
-                        Cc.class_count[c * kCountStride] = 0;          // short entries, from the front
-                        Cc.class_count[c * kCountStride + 1u] = 0;     // long entries, from the back
-                        Cc.class_miss[atomicAdd(&Cc.ctr->n_class_miss, 1u)] = c;
-                    }
+            }
+            Cc.miss[idx] = me;
+            if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
+                const uint32_t c = d.cls;
+                const uint32_t oc = __hip_atomic_load(&Cc.class_built[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (oc != epoch && atomicCAS(&Cc.class_built[c], oc, epoch) == oc) {
+                    Cc.class_count[c * kCountStride] = 0;          // short entries, from the front
+                    Cc.class_count[c * kCountStride + 1u] = 0;     // long entries, from the back
+                    Cc.class_miss[atomicAdd(&Cc.ctr->n_class_miss, 1u)] = c;
                 }
             }
         }
-        Cc.key_of[b] = key;
     }
-    unsigned long long hv = __ballot(hit), lv = __ballot(live);
-    if ((threadIdx.x & 63u) == 0) {
+    const unsigned long long hv = __ballot(hit), lv = __ballot(live);
+    if (lane == 0) {
         atomicAdd(&Cc.ctr->lookups, (unsigned long long)__popcll(lv));
         atomicAdd(&Cc.ctr->hits, (unsigned long long)__popcll(hv));
     }
@@ -316,7 +342,7 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
             seg[side][16] = sum;
         }
         __syncthreads();
-        ExitEntry *out = Cc.class_entries + (size_t)c * V;
+        ExitEntry *out = Cc.class_entries[c];
 #pragma unroll
         for (int s = 0; s < 4; s++) {
             const bool sh = (bx[s] >> lane) & 1ull, lg = (by[s] >> lane) & 1ull;
@@ -385,7 +411,7 @@ __device__ __forceinline__ bool walk_first_hop(const DeviceTable &T, const HopSt
 }
 
 __global__ void __launch_bounds__(1024)
-key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
+key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__restrict__ bitmask)
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t row[];
     __shared__ __attribute__((aligned(16))) uint8_t hop_lut[2][256];
@@ -402,7 +428,7 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
             ents = Vc.lit_entries + me.ent_lo;
             cnt = me.ent_cnt;
         } else if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
-            ents = Cc.class_entries + (size_t)me.cls * V;
+            ents = Cc.class_entries[me.cls];
             n_front = Cc.class_count[me.cls * kCountStride];
             cnt = n_front + Cc.class_count[me.cls * kCountStride + 1u];
             back = V - cnt;                           // index i >= n_front lives at i + back
@@ -480,35 +506,60 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
         if (tid == 0 && Vc.eos_id >= 0 && me.eos_next != WG_SID_ERROR)
             row[(uint32_t)Vc.eos_id >> 5] |= 1u << ((uint32_t)Vc.eos_id & 31u);
         __syncthreads();
-        // (c)
-        uint4 *dst = reinterpret_cast<uint4 *>(Cc.arena + (size_t)me.key * rs);
-        for (uint32_t q = tid; q < rs4; q += blockDim.x) dst[q] = row4[q];
+        // (c) to its arena row, or, if the arena had no row left, to the claimer's bitmask row
+        if (me.slot != kNoSlot) {
+            uint4 *dst = reinterpret_cast<uint4 *>(Cc.arena + (size_t)me.slot * rs);
+            for (uint32_t q = tid; q < rs4; q += blockDim.x) dst[q] = row4[q];
+            if (tid == 0) Cc.tags[me.key] = ((unsigned long long)Cc.epoch << 32) | me.slot;
+        } else {
+            uint32_t *dst = bitmask + (size_t)me.req * Vc.W;
+            for (uint32_t w = tid; w < Vc.W; w += blockDim.x) dst[w] = row[w];
+        }
         __syncthreads();
     }
     if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&Cc.ctr->builds, (unsigned long long)n_miss);
 }
 
-// gather: bitmask[b] <- the cached row of request b's key (zeros without a key).  Rows are copied
-// 16 bytes per thread when the caller's row stride allows it.
+// gather: bitmask[b] <- the row of request b's key (zeros without a key): from the arena, or
+// from the bitmask row of the request that built it when the row could not be kept.  Rows are
+// copied 16 bytes per thread when the caller's row stride allows it.
 template <bool kVec>
 __global__ void __launch_bounds__(256)
 gather_kernel(DeviceCache Cc, uint32_t W, uint32_t *__restrict__ bitmask)
 {
     const uint32_t b = blockIdx.y;
-    const uint32_t key = Cc.key_of[b];
-    const uint32_t *src = Cc.arena + (size_t)key * Cc.row_stride;
+    // The miss lists have been consumed by the kernels that ran before this one: count their
+    // rows as used and empty them for the next call.
+    if (blockIdx.x == 0 && b == 0 && threadIdx.x == 0) {
+        const unsigned long long sc = Cc.ctr->slot_ctr;
+        const uint32_t used = (uint32_t)(sc >> 32) == Cc.epoch ? (uint32_t)sc : 0u;
+        const uint32_t room = Cc.cap_rows - used, n = Cc.ctr->n_miss;
+        if (n > room) Cc.ctr->uncached_builds += n - room;
+        Cc.ctr->slot_ctr = ((unsigned long long)Cc.epoch << 32) | (used + (n < room ? n : room));
+        Cc.ctr->n_miss = 0; Cc.ctr->n_class_miss = 0;
+        Cc.ctr->launch++;
+    }
+    const uint32_t ref = Cc.row_ref[b];
+    const uint32_t *src = nullptr;
+    if (ref < kRefByKey) {
+        if (ref < Cc.cap_rows) src = Cc.arena + (size_t)ref * Cc.row_stride;   // cached before this call
+    } else if (ref != kNoKey) {
+        const unsigned long long t = Cc.tags[ref & ~kRefByKey];
+        if ((uint32_t)(t >> 32) == Cc.epoch) src = Cc.arena + (size_t)(uint32_t)t * Cc.row_stride;
+        else if ((uint32_t)(t & 0xFFFFu) == b) return;    // built in place by key_build
+        else if ((uint32_t)(t & 0xFFFFu) < gridDim.y)
+            src = bitmask + (size_t)(t & 0xFFFFu) * W;    // built for another request of this call
+    }
     uint32_t *dst = bitmask + (size_t)b * W;
     if (kVec) {
         const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
         uint4 *d4 = reinterpret_cast<uint4 *>(dst);
         for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < W / 4u; q += gridDim.x * blockDim.x)
-            d4[q] = key == kNoKey ? uint4{0u, 0u, 0u, 0u} : s4[q];
+            d4[q] = src ? s4[q] : uint4{0u, 0u, 0u, 0u};
     } else {
         for (uint32_t w = blockIdx.x * blockDim.x + threadIdx.x; w < W; w += gridDim.x * blockDim.x)
-            dst[w] = key == kNoKey ? 0u : src[w];
+            dst[w] = src ? src[w] : 0u;
     }
-    // the miss lists have been consumed by the kernels that ran before this one
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) { Cc.ctr->n_miss = 0; Cc.ctr->n_class_miss = 0; }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -787,7 +838,7 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
            ev ? ev + 2 : nullptr, T, Vc, Cc);
     uint32_t kb = n_cu * 2u;
     launch(key_build_kernel, dim3(B < kb ? B : kb), dim3(1024), Cc.row_stride * 4u, s,
-           ev ? ev + 4 : nullptr, T, Vc, Cc);
+           ev ? ev + 4 : nullptr, T, Vc, Cc, bitmask);
     const bool vec = Vc.W % 4u == 0 && reinterpret_cast<uintptr_t>(bitmask) % 16 == 0;
     if (vec) launch(gather_kernel<true>, dim3(cdiv(Vc.W / 4u, 256), B), dim3(256), 0, s, ev ? ev + 6 : nullptr, Cc, Vc.W, bitmask);
     else launch(gather_kernel<false>, dim3(cdiv(Vc.W, 256 * 4), B), dim3(256), 0, s, ev ? ev + 6 : nullptr, Cc, Vc.W, bitmask);

@@ -404,53 +404,77 @@ class Flattener {
 
 }  // namespace
 
-void lower(const char *const *templates, const wg_args_t *args, uint32_t n, uint32_t flags,
-           uint32_t lmax, Table &t) {
-    t = Table{};
+struct LoweringState {
+    std::unordered_map<std::string, std::unique_ptr<Op>> parsed;     // static structures, by text
+    std::map<std::array<uint8_t, 256>, uint32_t> class_ids;
+};
+
+Lowering::Lowering(uint32_t flags, uint32_t lmax) : st_(new LoweringState) {
+    Table &t = table;
     t.flags = flags; t.lmax = lmax;
     StateDesc fin{};
     fin.kind_byte = WG_KIND_FINAL;
     fin.next_a = fin.next_b = WG_SID_ERROR;
     fin.eos_next = WG_SID_FINAL;
     fin.max = WG_UNBOUNDED;
+    fin.key_base = 0;
     t.states.push_back(fin);
     t.tmpl.push_back(0);
     t.lit.push_back(0);
+    t.key_count.push_back(1);
+    t.n_keys = 1;
     t.classes.assign(256, CLS_REJECT);                 // table 0: rejects every byte
+    st_->class_ids[std::array<uint8_t, 256>{}] = 0;
+}
 
-    std::unordered_map<std::string, std::unique_ptr<Op>> parsed;   // static structures, by text
-    std::map<std::array<uint8_t, 256>, uint32_t> class_ids;
-    class_ids[std::array<uint8_t, 256>{}] = 0;
+Lowering::~Lowering() { delete st_; }
+
+void Lowering::add(const char *const *templates, const wg_args_t *args, uint32_t n) {
+    Table &t = table;
+    const size_t n_states0 = t.states.size(), n_classes0 = t.classes.size() / 256, n_start0 = t.start.size();
+    const uint32_t n_keys0 = t.n_keys;
+    auto roll_back = [&]() {
+        t.states.resize(n_states0); t.tmpl.resize(n_states0); t.lit.resize(n_states0);
+        t.key_count.resize(n_states0); t.start.resize(n_start0); t.classes.resize(n_classes0 * 256);
+        t.n_keys = n_keys0;
+        for (auto it = st_->class_ids.begin(); it != st_->class_ids.end();)
+            it = it->second >= n_classes0 ? st_->class_ids.erase(it) : std::next(it);
+    };
     for (uint32_t i = 0; i < n; i++) {
         try {
             if (!templates[i]) throw ParseError("null template text");
             std::string text(templates[i]);
-            auto it = parsed.find(text);
-            if (it == parsed.end()) {
+            auto it = st_->parsed.find(text);
+            if (it == st_->parsed.end()) {
                 Reader r(templates[i]);
-                it = parsed.emplace(text, r.parse_all()).first;
+                it = st_->parsed.emplace(text, r.parse_all()).first;
             }
-            Flattener f(t, args ? &args[i] : nullptr, i);
-            f.class_ids_.swap(class_ids);
-            uint32_t start = f.run(it->second.get());
-            f.class_ids_.swap(class_ids);
-            uint32_t after_eos = (flags & WG_EOS_RESTART) ? start : WG_SID_FINAL;
+            Flattener f(t, args ? &args[i] : nullptr, static_cast<uint32_t>(t.start.size()));
+            f.class_ids_.swap(st_->class_ids);
+            uint32_t start;
+            try { start = f.run(it->second.get()); }
+            catch (...) { f.class_ids_.swap(st_->class_ids); throw; }
+            f.class_ids_.swap(st_->class_ids);
+            uint32_t after_eos = (t.flags & WG_EOS_RESTART) ? start : WG_SID_FINAL;
             t.states[f.end_state()].eos_next = after_eos;
             for (uint32_t s : f.eos_exits()) t.states[s].eos_next = after_eos;
             t.start.push_back(start);
         } catch (const ParseError &e) {
+            roll_back();
             throw std::runtime_error("template " + std::to_string(i) + ": " + e.what());
+        } catch (...) {
+            roll_back();
+            throw;
         }
     }
-    t.lit.resize(((t.lit.size() + 7) & ~size_t(7)) + 16, 0);   // whole 8-byte words past the end
     // cache keys: one mask per state, lmax+1 for a bounded Wait (one per remaining budget
     // 0..lmax; a larger budget cannot bind inside a single token)
     t.key_count.resize(t.states.size());
-    uint32_t k = 0;
-    for (size_t s = 0; s < t.states.size(); s++) {
+    uint32_t k = n_keys0;
+    for (size_t s = n_states0; s < t.states.size(); s++) {
         StateDesc &d = t.states[s];
         bool bounded = (d.kind_byte & 0xFF) == WG_KIND_WAIT && d.max != WG_UNBOUNDED;
-        t.key_count[s] = bounded ? lmax + 1 : 1;
+        t.key_count[s] = bounded ? t.lmax + 1 : 1;
         d.key_base = k;
         k += t.key_count[s];
     }

@@ -305,6 +305,100 @@ def test_batch_larger_than_any_before_grows_the_call_scratch(torch_cuda):
     assert (H.host_mask(d_small) == o.fill_masks(H.start_states(o, w)[:100])).all()
 
 
+def _pick_tokens(o_rows, draws):
+    """The sampler stand-in on the host: the (draw mod popcount)-th allowed token of each row."""
+    out = np.full(len(o_rows), -1, dtype=np.int32)
+    for b, row in enumerate(o_rows):
+        pop = int(np.unpackbits(row.view(np.uint8)).sum())
+        if pop:
+            out[b] = O.select_bit(row, int(draws[b]) % pop)
+    return out
+
+
+def test_small_cache_serves_overflow_keys_uncached(torch_cuda):
+    """With fewer cache rows than distinct keys the surplus rows are built straight into the
+    callers' bitmask (also for the other requests of the call that share the key) and every
+    mask still equals the oracle's; a resize makes room again."""
+    torch = torch_cuda
+    w = ws.make_workload(5, V=3001, B=192, steps=10)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    h.cache_resize(7)
+    cur = H.start_states(o, w)
+    toks, sts, n_masks = o.trajectory(cur, w.token_draws(10))
+    d_states = H.dev_states(cur)
+    d_mask = torch.empty((w.B, h.W), dtype=torch.int32, device="cuda")
+    for k in range(10):
+        print("overflow step %d" % k, flush=True)
+        d_mask.fill_(0x5A5A5A5A)
+        h.fill_masks(d_states, d_mask)
+        assert (H.host_mask(d_mask) == o.fill_masks(cur)).all(), k
+        h.advance(d_states, torch.from_numpy(toks[k]).cuda())
+        cur = sts[k]
+    s = h.cache_stats()
+    assert s["cache_rows"] == 7 and s["rows_in_use"] == 7
+    assert s["uncached_builds"] > 0 and s["builds"] > n_masks       # overflow keys are rebuilt
+    assert s["lookups"] == 10 * w.B
+    # room for everything: every key is built once and then hit
+    h.cache_resize(4096)
+    cur = H.start_states(o, w)
+    d_states = H.dev_states(cur)
+    base = h.cache_stats()
+    for k in range(10):
+        h.fill_masks(d_states, d_mask)
+        assert (H.host_mask(d_mask) == o.fill_masks(cur)).all(), k
+        h.advance(d_states, torch.from_numpy(toks[k]).cuda())
+        cur = sts[k]
+    s2 = h.cache_stats()
+    assert s2["uncached_builds"] == base["uncached_builds"]
+    assert s2["builds"] - base["builds"] == s2["rows_in_use"] <= n_masks
+    assert h.error_count() == 0
+
+
+def test_instances_join_a_live_handle(torch_cuda):
+    """Requests arrive while the batch is running: their instances are added to the handle, the
+    running requests keep their states and cached rows, and every mask and state equals those of
+    an oracle that compiled all instances at once.  Starting from one instance, the 64 instances
+    outgrow the room reserved for states, keys and class tables, so the tables move as well."""
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    w = ws.make_workload(4, V=3001, B=64, steps=14)
+    n_inst = len(w.texts)
+    assert (np.asarray(w.request_template) == np.arange(w.B)).all() and n_inst == w.B
+    o = H.make_oracle(w)
+    gv = wg.Vocab(w.vocab.bytes, w.vocab.offsets, w.vocab.eos_id)
+    h = wg.Handle(w.texts[:1], w.args[:1], gv)
+    cur = H.start_states(o, w)
+    assert (h.start_states[0] == cur[0]).all()
+    draws = w.token_draws(14)
+    joined = 1
+    schedule = {2: 3, 4: 9, 5: 10, 7: 40, 10: 64}             # step -> instances present from then on
+    d_mask = torch.empty((w.B, h.W), dtype=torch.int32, device="cuda")
+    for k in range(14):
+        print("join step %d, %d instances" % (k, joined), flush=True)
+        if k in schedule:
+            with pytest.raises(wg.WgError):                  # a request with a broken template is refused ...
+                h.add_instances(["Sequence(Write(\"a\"), Wait(allow={b}))"], [{}])
+            new = h.add_instances(w.texts[joined:schedule[k]], w.args[joined:schedule[k]])
+            assert (new == cur[joined:schedule[k]]).all()    # ... and leaves the numbering alone
+            joined = schedule[k]
+            assert h.num_instances() == joined
+        act = cur[:joined]
+        d_states = H.dev_states(act)
+        h.fill_masks(d_states, d_mask[:joined])
+        want = o.fill_masks(act)
+        assert (H.host_mask(d_mask[:joined]) == want).all(), k
+        tok = _pick_tokens(want, draws[k])
+        h.advance(d_states, torch.from_numpy(tok).cuda())
+        nxt = o.advance(act, tok)
+        assert (H.host_states(d_states) == nxt).all(), k
+        cur[:joined] = nxt
+    assert h.num_states == o.num_states and h.error_count() == 0
+    # nothing was rebuilt because of the joins: as many builds as distinct keys were seen
+    s = h.cache_stats()
+    assert s["uncached_builds"] == 0 and s["builds"] == s["rows_in_use"]
+
+
 def test_two_handles_share_one_vocabulary(torch_cuda):
     torch = torch_cuda
     import paper_2507_16768_amd as wg

@@ -40,9 +40,9 @@ def test_product_package_does_not_reach_for_the_oracle():
             assert "paper_2507_16768_amd" not in text and "libwgrammar" not in text, fn
 
 
-def _same_machine(texts, args, restart, lmax=8):
+def _same_machine(texts, args, restart, lmax=8, table=None):
     o = O.Oracle(texts, args, None, restart=restart)
-    t = wg.Table(texts, args, flags=wg.EOS_RESTART if restart else wg.EOS_STOP, lmax=lmax)
+    t = table or wg.Table(texts, args, flags=wg.EOS_RESTART if restart else wg.EOS_STOP, lmax=lmax)
     assert t.num_states == o.num_states
     for i in range(len(texts)):
         assert t.start_state(i) == o.start_state(i)
@@ -91,6 +91,28 @@ def test_lowering_matches_oracle_on_random_trees(restart, golden_dir):
     with open(os.path.join(golden_dir, "worked_example_template.txt")) as f:
         text = "".join(l for l in f if not l.startswith("#"))
     assert _same_machine([text], None, restart) == 6
+
+
+def test_instances_appended_one_by_one_give_the_same_table():
+    """Adding instances to a live table numbers them exactly as compiling them together does,
+    and an add that fails to parse leaves nothing behind."""
+    for idx, kw in ((3, {}), (5, dict(B=24, V=1000))):
+        w = ws.make_workload(idx, **kw)
+        lmax = 24
+        t = wg.Table(w.texts[:1], w.args[:1] if w.args else None, flags=wg.EOS_RESTART, lmax=lmax)
+        i = 1
+        while i < len(w.texts):
+            n_before = (t.num_states, t.n_templates)
+            with pytest.raises(wg.WgError) as e:
+                t.add_instances([w.texts[i], "Sequence(Wait(allow={q}, wait={z}), Frobnicate())"],
+                                [w.args[i], {}] if w.args else None)
+            assert e.value.code == -2 and "template 1" in str(e.value)
+            assert (t.num_states, t.n_templates) == n_before
+            step = 1 + i % 3
+            t.add_instances(w.texts[i:i + step], w.args[i:i + step] if w.args else None)
+            i += step
+        assert t.n_templates == len(w.texts)
+        _same_machine(w.texts, w.args, True, lmax=lmax, table=t)
 
 
 @pytest.mark.parametrize("text,frag", [
