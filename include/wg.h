@@ -203,6 +203,13 @@ int wg_masked_argmax(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_
 int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B,
                void *stream);
 
+/* wg_advance_fill_masks: wg_advance followed by wg_fill_masks on the new states, for the decode
+ * loop, where the two always meet (the token sampled under step k's mask is consumed, then step
+ * k+1's mask is produced): same results, one kernel launch and one pass over the state
+ * descriptors fewer.  In wg_profile_read the combined first kernel is counted as the lookup. */
+int wg_advance_fill_masks(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B,
+                          uint32_t *d_bitmask, void *stream);
+
 /* Forget every cached mask row and every class-table index built from the operators' allow /
  * wait sets.  O(1) and launches nothing: the handle's cache generation is bumped on the host
  * and travels with every later call as a kernel argument (so a clear recorded into a HIP

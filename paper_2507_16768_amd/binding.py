@@ -56,7 +56,7 @@ EXPORTS = [
     "wg_apply_mask", "wg_advance", "wg_cache_clear", "wg_cache_stats", "wg_error_count",
     "wg_last_error", "wg_select_tokens", "wg_profile_enable", "wg_profile_read", "wg_masked_argmax",
     "wg_add_instances", "wg_num_instances", "wg_cache_resize", "wg_table_add_instances",
-    "wg_table_num_instances",
+    "wg_table_num_instances", "wg_advance_fill_masks",
 ]
 
 
@@ -105,6 +105,7 @@ def load_library():
     L.wg_fill_masks.argtypes = [vp, vp, u32, vp, vp]
     L.wg_apply_mask.argtypes = [vp, C.c_int, u32, u32, i64, vp, vp]
     L.wg_advance.argtypes = [vp, vp, vp, u32, vp]
+    L.wg_advance_fill_masks.argtypes = [vp, vp, vp, u32, vp, vp]
     L.wg_masked_argmax.argtypes = [vp, C.c_int, u32, u32, i64, vp, vp, vp]
     L.wg_cache_clear.argtypes = [vp, vp]
     L.wg_cache_stats.argtypes = [vp, C.POINTER(_Stats)]
@@ -250,6 +251,15 @@ class Handle:
             raise ValueError("states must be [B, 2] and tokens [B]")
         _check(load_library().wg_advance(self._h, _dev(states, torch.int32, "states"),
                                          _dev(tokens, torch.int32, "tokens"), B, _stream_ptr(stream)))
+
+    def advance_fill_masks(self, states, tokens, bitmask, stream=None):
+        import torch
+        B = states.shape[0]
+        if tuple(states.shape) != (B, 2) or tuple(tokens.shape) != (B,) or tuple(bitmask.shape) != (B, self.W):
+            raise ValueError("states must be [B, 2], tokens [B] and bitmask [B, W]")
+        _check(load_library().wg_advance_fill_masks(
+            self._h, _dev(states, torch.int32, "states"), _dev(tokens, torch.int32, "tokens"), B,
+            _dev(bitmask, torch.int32, "bitmask"), _stream_ptr(stream)))
 
     def add_instances(self, texts, args, stream=None):
         """wg_add_instances: returns the start states [n, 2] of the new instances."""

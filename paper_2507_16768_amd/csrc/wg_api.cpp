@@ -486,18 +486,33 @@ uint32_t wg_mask_words(wg_handle_t h) { return h ? h->vocab->dv.W : 0; }
 
 // ---- per-step calls -----------------------------------------------------------------------------
 
-int wg_fill_masks(wg_handle_t h, const wg_state_t *d_states, uint32_t B, uint32_t *d_bitmask,
-                  void *stream) {
-    if (!h || !d_states || !d_bitmask) return fail(WG_ERR_INVALID, "wg_fill_masks: null argument");
-    if (B == 0) return fail(WG_ERR_INVALID, "wg_fill_masks: B is 0");
-    if (B > kMaxBatch) return fail(WG_ERR_INVALID, "wg_fill_masks: B above 65535");
+namespace {
+int fill(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B, uint32_t *d_bitmask,
+         void *stream, const char *who) {
+    if (B == 0) return fail(WG_ERR_INVALID, std::string(who) + ": B is 0");
+    if (B > kMaxBatch) return fail(WG_ERR_INVALID, std::string(who) + ": B above 65535");
     int rc = ensure_batch(h, B);
     if (rc != WG_OK) return rc;
     hipEvent_t ev[8];
     if (h->profiling) for (auto &e : ev) { e = take_event(h); h->fill_events.push_back(e); }
-    WG_HIP(launch_fill(h->dt, h->vocab->dv, h->dc, d_states, B, d_bitmask, h->n_cu,
+    WG_HIP(launch_fill(h->dt, h->vocab->dv, h->dc, d_states, d_tokens, B, d_bitmask, h->n_cu,
                        static_cast<hipStream_t>(stream), h->profiling ? ev : nullptr));
     return WG_OK;
+}
+}  // namespace
+
+int wg_fill_masks(wg_handle_t h, const wg_state_t *d_states, uint32_t B, uint32_t *d_bitmask,
+                  void *stream) {
+    if (!h || !d_states || !d_bitmask) return fail(WG_ERR_INVALID, "wg_fill_masks: null argument");
+    // the states are only read when no tokens are given
+    return fill(h, const_cast<wg_state_t *>(d_states), nullptr, B, d_bitmask, stream, "wg_fill_masks");
+}
+
+int wg_advance_fill_masks(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B,
+                          uint32_t *d_bitmask, void *stream) {
+    if (!h || !d_states || !d_tokens || !d_bitmask)
+        return fail(WG_ERR_INVALID, "wg_advance_fill_masks: null argument");
+    return fill(h, d_states, d_tokens, B, d_bitmask, stream, "wg_advance_fill_masks");
 }
 
 int wg_apply_mask(void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V, int64_t row_stride_elems,

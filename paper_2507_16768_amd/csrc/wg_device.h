@@ -107,9 +107,10 @@ struct DeviceCache {
 };
 
 // ev, when not null, holds eight events: a begin / end pair for each of the four kernels of a fill.
+// With tokens != nullptr the states are first advanced by them (in place, in the lookup kernel).
 hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
-                       const wg_state_t *states, uint32_t B, uint32_t *bitmask, uint32_t n_cu,
-                       hipStream_t s, hipEvent_t *ev);
+                       wg_state_t *states, const int32_t *tokens, uint32_t B, uint32_t *bitmask,
+                       uint32_t n_cu, hipStream_t s, hipEvent_t *ev);
 hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
                         const uint32_t *bitmask, hipStream_t s);
 hipError_t launch_masked_argmax(const void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,

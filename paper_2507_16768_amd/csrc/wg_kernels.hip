@@ -139,21 +139,32 @@ __device__ __forceinline__ bool walk_chunks(const DeviceTable &T, uint32_t &sid,
 // checkpoint whose class table has no index yet in this generation, the table is claimed and
 // queued for class_scan.
 
-__global__ void __launch_bounds__(64)
-lookup_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, const wg_state_t *__restrict__ states, uint32_t B)
+// What a lookup reads from the handle's counters before anything depends on it.
+struct LookupEnv {
+    unsigned long long launch;   // number of this fill call
+    uint32_t rows0;              // arena rows in use before this call
+};
+
+__device__ __forceinline__ LookupEnv lookup_env(const DeviceCache &Cc)
 {
-    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x, lane = threadIdx.x & 63u;
-    const bool live = b < B;
-    bool hit = false, claimed = false;
-    uint32_t sid = 0, aux = 0, key = kNoKey, kind = 0, variant = 0;
-    const uint32_t epoch = Cc.epoch;
-    const unsigned long long launch = Cc.ctr->launch & kTagLaunchMask;
     const unsigned long long sc = Cc.ctr->slot_ctr;
-    const uint32_t rows0 = (uint32_t)(sc >> 32) == epoch ? (uint32_t)sc : 0u;   // rows in use before this call
+    return LookupEnv{Cc.ctr->launch & kTagLaunchMask, (uint32_t)(sc >> 32) == Cc.epoch ? (uint32_t)sc : 0u};
+}
+
+// The lookup of request b in state (sid, aux); every lane of the wavefront calls it, `live`
+// says whether the lane has a request.
+__device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
+                                           const LookupEnv &env, uint32_t b, bool live, uint32_t sid, uint32_t aux)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    bool hit = false, claimed = false;
+    uint32_t key = kNoKey, kind = 0, variant = 0;
+    const uint32_t epoch = Cc.epoch;
+    const unsigned long long launch = env.launch;
+    const uint32_t rows0 = env.rows0;
     uint32_t ref = kNoKey;
     StateDesc d{};
     if (live) {
-        sid = states[b].sid; aux = states[b].aux;
         if (sid < T.n_states) {
             d = T.states[sid];
             kind = d.kind_byte & 0xFFu;
@@ -219,6 +230,17 @@ lookup_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, const wg_state_t *_
         atomicAdd(&Cc.ctr->lookups, (unsigned long long)__popcll(lv));
         atomicAdd(&Cc.ctr->hits, (unsigned long long)__popcll(hv));
     }
+}
+
+__global__ void __launch_bounds__(64)
+lookup_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, const wg_state_t *__restrict__ states, uint32_t B)
+{
+    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = b < B;
+    const LookupEnv env = lookup_env(Cc);
+    uint32_t sid = 0, aux = 0;
+    if (live) { sid = states[b].sid; aux = states[b].aux; }
+    lookup_one(T, Vc, Cc, env, b, live, sid, aux);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -742,14 +764,9 @@ apply_scalar_kernel(Elem *__restrict__ logits, int64_t row_stride, uint32_t V, u
 // advance: one thread per request.  The token's bytes are fetched as 8-byte chunks (three
 // independent loads) and walked with walk_chunks; tokens longer than 24 bytes take the
 // generic byte-at-a-time walker.
-__global__ void __launch_bounds__(64)
-advance_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, wg_state_t *__restrict__ states,
-               const int32_t *__restrict__ tokens, uint32_t B)
+__device__ __forceinline__ void advance_one(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
+                                            uint32_t &sid, uint32_t &aux, int64_t t)
 {
-    uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= B) return;
-    uint32_t sid = states[b].sid, aux = states[b].aux;
-    const int64_t t = (int64_t)tokens[b];
     bool ok;
     if (Vc.lmax > 24u || t < 0 || t >= (int64_t)Vc.V || (int64_t)Vc.eos_id == t) {
         ok = walk_token(T, Vc, sid, aux, t);
@@ -760,11 +777,39 @@ advance_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, wg_state_t *__rest
         const uint64_t c2 = Vc.n_chunks > 2u ? Vc.chunks[2ull * Vc.V + t] : 0ull;
         ok = L != 0u && sid < T.n_states && walk_chunks(T, sid, aux, c0, c1, c2, 0u, L);
     }
-    if (ok) { states[b].sid = sid; states[b].aux = aux; }
-    else {
-        states[b].sid = WG_SID_ERROR; states[b].aux = 0;
+    if (!ok) {
+        sid = WG_SID_ERROR; aux = 0;
         atomicAdd(&Cc.ctr->errors, 1ull);
     }
+}
+
+__global__ void __launch_bounds__(64)
+advance_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, wg_state_t *__restrict__ states,
+               const int32_t *__restrict__ tokens, uint32_t B)
+{
+    uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    uint32_t sid = states[b].sid, aux = states[b].aux;
+    advance_one(T, Vc, Cc, sid, aux, (int64_t)tokens[b]);
+    states[b].sid = sid; states[b].aux = aux;
+}
+
+// advance followed by the lookup of the next step's fill, one thread per request: the new
+// state goes straight from the walker into the cache lookup.
+__global__ void __launch_bounds__(64)
+advance_lookup_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, wg_state_t *__restrict__ states,
+                      const int32_t *__restrict__ tokens, uint32_t B)
+{
+    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = b < B;
+    const LookupEnv env = lookup_env(Cc);
+    uint32_t sid = 0, aux = 0;
+    if (live) {
+        sid = states[b].sid; aux = states[b].aux;
+        advance_one(T, Vc, Cc, sid, aux, (int64_t)tokens[b]);
+        states[b].sid = sid; states[b].aux = aux;
+    }
+    lookup_one(T, Vc, Cc, env, b, live, sid, aux);
 }
 
 // One block per row: d_tokens[b] = index of the (draw mod popcount)-th set bit.
@@ -825,10 +870,11 @@ static inline void launch(K kernel, dim3 grid, dim3 block, uint32_t lds, hipStre
 }
 
 hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
-                       const wg_state_t *states, uint32_t B, uint32_t *bitmask, uint32_t n_cu,
-                       hipStream_t s, hipEvent_t *ev)
+                       wg_state_t *states, const int32_t *tokens, uint32_t B, uint32_t *bitmask,
+                       uint32_t n_cu, hipStream_t s, hipEvent_t *ev)
 {
-    launch(lookup_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s, ev, T, Vc, Cc, states, B);
+    if (tokens) launch(advance_lookup_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s, ev, T, Vc, Cc, states, tokens, B);
+    else launch(lookup_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s, ev, T, Vc, Cc, static_cast<const wg_state_t *>(states), B);
     // the number of misses is only known on the device: both build kernels stride a fixed
     // grid over whatever the lookup queued and fall through when nothing is queued
     uint32_t groups = cdiv(Vc.V, kScanGroup);

@@ -21,8 +21,9 @@ def torch_cuda():
     return torch
 
 
-def _replay(torch, w, steps, check_logits_every=1, label=""):
-    """Oracle generates the trajectory; the GPU replays it step by step."""
+def _replay(torch, w, steps, check_logits_every=1, label="", fused=False):
+    """Oracle generates the trajectory; the GPU replays it step by step (with fused=True through
+    wg_advance_fill_masks instead of wg_advance + wg_fill_masks)."""
     import paper_2507_16768_amd as wg
     o = H.make_oracle(w)
     v, h = H.make_gpu(w)
@@ -36,7 +37,8 @@ def _replay(torch, w, steps, check_logits_every=1, label=""):
     seen = {}
     for k in range(steps):
         print("%s step %d" % (label, k), flush=True) if k % 16 == 0 else None
-        h.fill_masks(d_states, d_mask)
+        if not fused or k == 0:
+            h.fill_masks(d_states, d_mask)
         got = H.host_mask(d_mask)
         for b in range(B):
             key = (int(cur[b, 0]), int(cur[b, 1]))
@@ -51,7 +53,11 @@ def _replay(torch, w, steps, check_logits_every=1, label=""):
             want_bits = want.view(np.uint32) if want.dtype == np.float32 else want
             assert (H.host_logit_bits(d_log) == want_bits).all(), (label, k)
         d_tok = torch.from_numpy(toks[k]).cuda()
-        h.advance(d_states, d_tok)
+        if fused and k + 1 < steps:
+            d_mask.fill_(0x3C3C3C3C)
+            h.advance_fill_masks(d_states, d_tok, d_mask)
+        else:
+            h.advance(d_states, d_tok)
         cur = o.advance(cur, toks[k])
         assert (cur == sts[k]).all()
         assert (H.host_states(d_states) == cur).all(), (label, k)
@@ -109,6 +115,28 @@ def test_full_size_configs_sampled(torch_cuda, idx, B, steps):
     w = ws.make_workload(idx, steps=steps)
     assert w.B == B
     _replay(torch_cuda, w, steps, check_logits_every=max(1, steps // 2), label="cfg%d-full" % idx)
+
+
+@pytest.mark.parametrize("idx,V,B,steps", [(3, 3001, 8, 48), (5, 4099, 96, 24)])
+def test_fused_advance_and_fill_match_the_separate_calls(torch_cuda, idx, V, B, steps):
+    w = ws.make_workload(idx, V=V, B=B, steps=steps)
+    h, o, nkeys = _replay(torch_cuda, w, steps, check_logits_every=8, label="fused cfg%d" % idx, fused=True)
+    s = h.cache_stats()
+    assert s["lookups"] == steps * B and s["builds"] == nkeys == s["rows_in_use"]
+    # an illegal token in the fused call: the request goes to ERROR and gets a row of zeros
+    torch = torch_cuda
+    st = H.start_states(o, w)
+    row = o.mask_row(tuple(st[0]))
+    bad = next(t for t in range(w.vocab.V) if not (row[t >> 5] >> (t & 31)) & 1)
+    good = O.select_bit(row, 0)
+    d_states = H.dev_states(st[:2].copy() * 0 + st[0])
+    d_mask = torch.empty((2, h.W), dtype=torch.int32, device="cuda")
+    h.advance_fill_masks(d_states, torch.tensor([bad, good], dtype=torch.int32, device="cuda"), d_mask)
+    got_s, got_m = H.host_states(d_states), H.host_mask(d_mask)
+    nxt = o.advance(st[:1], [good])
+    assert tuple(got_s[0]) == (0xFFFFFFFF, 0) and not got_m[0].any()
+    assert (got_s[1] == nxt[0]).all() and (got_m[1] == o.mask_row(tuple(nxt[0]))).all()
+    assert h.error_count() == 1
 
 
 def test_long_tokens_take_the_generic_paths(torch_cuda):
