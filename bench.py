@@ -42,31 +42,64 @@ def kernel_source_sha256():
         return hashlib.sha256(f.read()).hexdigest()
 
 
-def cpu_baseline(w, n_steps):
-    """The CPU oracle, as it stands, on the first n_steps steps of the same workload:
-    un-memoised mask rows for every request, masking of a [B, V] logits buffer, token
-    choice and advance.  Single thread."""
+def _oracle_steps(w, lo, hi, n_steps):
+    """Requests lo..hi-1 of the workload for n_steps steps through the CPU oracle: un-memoised
+    mask rows, masking of a logits buffer, token choice and advance.  Returns the seconds spent."""
     import wg_synth as ws
     from oracle import oracle as O
 
     ov = O.OracleVocab(w.vocab.bytes, w.vocab.offsets, w.vocab.eos_id)
     o = O.Oracle(w.texts, w.args, ov, restart=True)
-    cur = np.array([[o.start_state(int(t)), 0] for t in w.request_template], dtype=np.uint32)
-    draws = w.token_draws(n_steps)
-    logits = ws.to_bf16_bits(ws.make_logits(w.seed, w.B, w.vocab.V, w.sigma))
+    n = hi - lo
+    cur = np.array([[o.start_state(int(t)), 0] for t in w.request_template[lo:hi]], dtype=np.uint32)
+    draws = w.token_draws(n_steps)[:, lo:hi]
+    logits = ws.to_bf16_bits(ws.make_logits(w.seed, n, w.vocab.V, w.sigma))
     t0 = time.perf_counter()
     for k in range(n_steps):
         masks = o.fill_masks(cur)
         O.apply_mask(logits, masks)
-        toks = np.empty(w.B, dtype=np.int32)
-        for b in range(w.B):
+        toks = np.empty(n, dtype=np.int32)
+        for b in range(n):
             pop = int(np.unpackbits(masks[b].view(np.uint8)).sum())
             toks[b] = O.select_bit(masks[b], int(draws[k, b] % np.uint64(max(pop, 1))))
         cur = o.advance(cur, toks)
-    dt = time.perf_counter() - t0
-    return {"value": w.B * n_steps / dt, "unit": "request-steps/s", "cores": 1, "kind": "oracle",
-            "sample": "first %d steps of the same workload (%d request-steps, cold: every mask "
-                      "rebuilt), %.1f s" % (n_steps, w.B * n_steps, dt)}
+    return time.perf_counter() - t0
+
+
+_fork_workload = None      # set before the worker pool forks, so that the jobs carry indexes only
+
+
+def _oracle_worker(job):
+    return _oracle_steps(_fork_workload, *job)
+
+
+def cpu_baseline(w, n_steps):
+    """The CPU oracle, as it stands, on the first n_steps steps of the same workload, on one
+    thread; then independent copies of it on disjoint request ranges, one per host core (the
+    work is independent per request), for an all-cores figure.  Call it before the process
+    touches the GPU: the all-cores leg forks."""
+    import multiprocessing as mp
+
+    dt = _oracle_steps(w, 0, w.B, n_steps)
+    out = {"value": w.B * n_steps / dt, "unit": "request-steps/s", "cores": 1, "kind": "oracle",
+           "sample": "first %d steps of the same workload (%d request-steps, cold: every mask "
+                     "rebuilt), %.1f s" % (n_steps, w.B * n_steps, dt)}
+    cores = min(16, len(os.sched_getaffinity(0)), w.B)
+    if cores > 1:
+        steps_all = n_steps * 4
+        cuts = [w.B * i // cores for i in range(cores + 1)]
+        jobs = [(cuts[i], cuts[i + 1], steps_all) for i in range(cores)]
+        global _fork_workload
+        _fork_workload = w
+        t0 = time.perf_counter()
+        with mp.get_context("fork").Pool(cores) as pool:
+            spent = pool.map(_oracle_worker, jobs)
+        wall = time.perf_counter() - t0
+        out["all_cores"] = {"value": w.B * steps_all / max(spent), "unit": "request-steps/s", "cores": cores,
+                            "sample": "first %d steps, the %d requests split over %d processes; slowest "
+                                      "process %.1f s (%.1f s with start-up)"
+                                      % (steps_all, w.B, cores, max(spent), wall)}
+    return out
 
 
 def main():
@@ -83,9 +116,14 @@ def main():
               % args.gpus, file=sys.stderr)
         sys.exit(2)
 
+    import wg_synth as ws
+
+    w = ws.make_workload(args.config)
+    # the CPU legs run first: they fork worker processes, which is done before the GPU is initialised
+    cpu = cpu_baseline(w, args.cpu_steps) if args.cpu_steps > 0 else None
+
     import torch
     import paper_2507_16768_amd as wg
-    import wg_synth as ws
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -94,7 +132,6 @@ def main():
     torch.cuda.set_device(0)
     K, Wm = args.steps, args.warmup
     total = K + Wm
-    w = ws.make_workload(args.config)
     B, V = w.B, w.vocab.V
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
     esz = 4 if w.dtype == "f32" else 2
@@ -155,15 +192,12 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / K
 
-    # every key was cached by the pre-pass; the warm step is short enough for host launch jitter
-    # to show, so it is the best of three timed passes (the cold headline below is a single pass)
-    sec_warm = min(timed(False) for _ in range(3))
-    s0 = h.cache_stats()
-    sec_cold = timed(True)
-    s1 = h.cache_stats()
-    builds_per_step = (s1["builds"] - s0["builds"]) / float(total)
-    scans_per_step = (s1["class_scans"] - s0["class_scans"]) / float(total)
-    entries_per_step = (s1["entries_walked"] - s0["entries_walked"]) / float(total)
+    def step(cold, k):
+        if cold:
+            h.cache_clear()
+        h.fill_masks(states, mask)
+        wg.apply_mask(ring[k & 3], mask)
+        h.advance(states, tokens[k])
 
     # ---- per-kernel durations over the same timed region, HIP events on the launch stream ----
     def kernel_times(cold):
@@ -175,18 +209,66 @@ def main():
         h.profile_enable(True)
         h.profile_read()
         for k in range(Wm, total):
-            if cold:
-                h.cache_clear()
-            h.fill_masks(states, mask)
-            wg.apply_mask(ring[k & 3], mask)
-            h.advance(states, tokens[k])
+            step(cold, k)
         torch.cuda.synchronize()
         p = h.profile_read()
         h.profile_enable(False)
         return {k[:-3] + "_us": 1e3 * p[k] / K for k in ("lookup_ms", "scan_ms", "build_ms", "gather_ms", "advance_ms")}
 
-    kt_cold = kernel_times(True)
+    # ---- spread of the step time: one event per step boundary (their cost is inside the figures) ----
+    def step_spread(cold):
+        states.copy_(start)
+        if cold:
+            h.cache_clear()
+        run(cold, 0, Wm)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for k in range(Wm, total):
+            step(cold, k)
+            ev[k - Wm + 1].record()
+        torch.cuda.synchronize()
+        us = np.array([1e3 * ev[i].elapsed_time(ev[i + 1]) for i in range(K)])
+        return {"median_us": float(np.median(us)), "p10_us": float(np.percentile(us, 10)),
+                "p90_us": float(np.percentile(us, 90))}
+
+    # ---- the decode loop with advance and the next fill in one call ----
+    def timed_fused(cold):
+        def go(lo, hi):
+            for k in range(lo, hi):
+                wg.apply_mask(ring[k & 3], mask)
+                if cold:
+                    h.cache_clear()
+                h.advance_fill_masks(states, tokens[k], mask)
+        states.copy_(start)
+        if cold:
+            h.cache_clear()
+        h.fill_masks(states, mask)
+        go(0, Wm)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        go(Wm, total)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / K
+
+    # Warm first: every key was cached by the pre-pass.  The warm step is short enough for host
+    # launch jitter to show, so it is the best of three timed passes (the cold headline below is
+    # a single pass).
+    sec_warm = min(timed(False) for _ in range(3))
     kt_warm = kernel_times(False)
+    spread_warm = step_spread(False)
+    assert h.cache_stats()["builds"] == pre["builds"], "a warm pass built a mask"
+    # (the fused loop also fills for the state after the last step, which no pass before it saw)
+    sec_fused_warm = min(timed_fused(False) for _ in range(3))
+    s0 = h.cache_stats()
+    sec_cold = timed(True)
+    s1 = h.cache_stats()
+    builds_per_step = (s1["builds"] - s0["builds"]) / float(total)
+    scans_per_step = (s1["class_scans"] - s0["class_scans"]) / float(total)
+    entries_per_step = (s1["entries_walked"] - s0["entries_walked"]) / float(total)
+    kt_cold = kernel_times(True)
+    spread_cold = step_spread(True)
+    sec_fused_cold = timed_fused(True)
     # apply is a single kernel outside the handle: time a back-to-back run of it
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -201,8 +283,8 @@ def main():
     # ---- greedy variant of the step: fill, masked argmax (logits only read), advance ----
     greedy_tok = torch.empty(B, dtype=torch.int32, device="cuda")
 
-    def run_greedy(cold, n):
-        for k in range(n):
+    def run_greedy(cold, lo, hi):
+        for k in range(lo, hi):
             if cold:
                 h.cache_clear()
             h.fill_masks(states, mask)
@@ -210,18 +292,23 @@ def main():
             h.advance(states, greedy_tok)
 
     def timed_greedy(cold):
+        if not cold:                                  # a first pass over the same trajectory caches its keys
+            states.copy_(start)
+            h.cache_clear()
+            run_greedy(False, 0, total)
         states.copy_(start)
-        h.cache_clear()
-        run_greedy(cold, Wm)
+        if cold:
+            h.cache_clear()
+        run_greedy(cold, 0, Wm)
         torch.cuda.synchronize()
         t = time.perf_counter()
-        run_greedy(cold, K)
+        run_greedy(cold, Wm, total)
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / K
 
     fresh = [(torch.randn((B, V), device="cuda", dtype=torch.float32) * w.sigma).to(tdt) for _ in range(4)]
     sec_greedy_cold = timed_greedy(True)
-    sec_greedy_warm = timed_greedy(False)      # revisits the states of the run before it
+    sec_greedy_warm = timed_greedy(False)
     assert h.error_count() == 0, "greedy decoding chose an illegal token"
     torch.cuda.synchronize()
     e0.record()
@@ -279,6 +366,13 @@ def main():
                      "traffic": TRAFFIC_BYTES[dominant] if kernel_source_sha256() == TRAFFIC_SOURCE_SHA256 else None,
                      "algorithmic_bytes_per_launch": dom_bytes, "us_per_launch": dom_us},
         "kernels_us_per_step": {"cold": kt_cold, "warm": kt_warm},
+        "step_spread": {"note": "per-step times between events recorded at the step boundaries "
+                                "(fill + apply + advance, event cost included)",
+                        "cold": spread_cold, "warm": spread_warm},
+        "fused_advance_fill": {"note": "the same steps through wg_apply_mask + wg_advance_fill_masks",
+                               "cold_ms_per_step": sec_fused_cold * 1e3, "warm_ms_per_step": sec_fused_warm * 1e3,
+                               "cold_request_steps_per_s": B / sec_fused_cold,
+                               "warm_request_steps_per_s": B / sec_fused_warm},
         "kernels_GBs": {k: (v[0] / (v[1] * 1e-6) / 1e9 if v[1] > 0 else None) for k, v in per_kernel.items()},
         "apply": {"disallowed_fraction": disallowed_per_step / float(B * V),
                   "min_bytes_GBs": apply_min_bytes / (apply_us * 1e-6) / 1e9,
@@ -291,8 +385,8 @@ def main():
         "compile_ms": compile_ms,
         "prepass": {"builds": pre["builds"], "lookups": pre["lookups"], "class_scans": pre["class_scans"]},
     }
-    if args.cpu_steps > 0:
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_steps)
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 
