@@ -132,6 +132,23 @@ void wg_vocab_destroy(wg_vocab_t v);
  * lmax is the longest token length the masks will be built for. */
 int wg_lower(const char *const *templates, const wg_args_t *args, uint32_t n_templates,
              uint32_t flags, uint32_t lmax, wg_table_t *out);
+/* wg_regex_to_template: a constraint given as a regular expression, turned into template text
+ * for wg_compile / wg_lower (the translation of the section "Operator Building and State
+ * Tracking": literals -> Write, classes -> Wait, * + ? | -> DoWhile / IfElse around condition
+ * Waits).  Bytes, not code points; the whole output must match; syntax: literals, escapes
+ * (\d \w \s \D \W \S \n \t \r \f \v \0 \xHH, \c for a punctuation byte c), '.', [..] and
+ * [^..] with ranges, ( ) and (?: ), |, * + ? {m} {m,} {m,n}, ^ and $ at the ends.  The operators
+ * decide on one byte, consume it, and have two ways out of a checkpoint, so an expression is
+ * refused (WG_ERR_PARSE, with the rule it breaks) unless: every optional or repeated group and
+ * each side of an alternation starts with a single byte or class; what follows such a group is
+ * a single byte or class or the end; the byte sets a decision tells apart, and a repeated
+ * class and its terminators, are disjoint; an alternation has two sides (any number when all
+ * are single bytes).  The text is written to out[0 .. capacity) with its terminating 0;
+ * *needed (may be NULL) receives the size required, also when capacity is too small
+ * (WG_ERR_INVALID).  The expression ends at the end of generation: its last checkpoint
+ * accepts <eos>. */
+int wg_regex_to_template(const char *regex, char *out, uint64_t capacity, uint64_t *needed);
+
 /* appends instances to a table, numbering their states after the existing ones (the host
  * half of wg_add_instances); on WG_ERR_PARSE the table is unchanged */
 int wg_table_add_instances(wg_table_t t, const char *const *templates, const wg_args_t *args,

@@ -56,7 +56,7 @@ EXPORTS = [
     "wg_apply_mask", "wg_advance", "wg_cache_clear", "wg_cache_stats", "wg_error_count",
     "wg_last_error", "wg_select_tokens", "wg_profile_enable", "wg_profile_read", "wg_masked_argmax",
     "wg_add_instances", "wg_num_instances", "wg_cache_resize", "wg_table_add_instances",
-    "wg_table_num_instances", "wg_advance_fill_masks",
+    "wg_table_num_instances", "wg_advance_fill_masks", "wg_regex_to_template",
 ]
 
 
@@ -83,6 +83,7 @@ def load_library():
     L.wg_table_add_instances.argtypes = [vp, C.POINTER(C.c_char_p), C.POINTER(_Args), u32]
     L.wg_table_num_instances.argtypes = [vp]
     L.wg_table_num_instances.restype = u32
+    L.wg_regex_to_template.argtypes = [C.c_char_p, C.c_char_p, u64, C.POINTER(u64)]
     L.wg_table_num_states.argtypes = [vp]
     L.wg_table_num_states.restype = u32
     L.wg_table_start_state.argtypes = [vp, u32]
@@ -161,6 +162,20 @@ def _dev(t, dtype=None, name="tensor"):
     if dtype is not None and t.dtype != dtype:
         raise ValueError("%s must have dtype %s" % (name, dtype))
     return C.c_void_p(t.data_ptr())
+
+
+def regex_to_template(regex):
+    """wg_regex_to_template: template text (str) for a regular expression (str or bytes)."""
+    L = load_library()
+    rx = regex.encode("utf-8") if isinstance(regex, str) else bytes(regex)
+    need = C.c_uint64(0)
+    buf = C.create_string_buffer(4096)
+    rc = L.wg_regex_to_template(rx, buf, len(buf), C.byref(need))
+    if rc != 0 and need.value > len(buf):
+        buf = C.create_string_buffer(need.value)
+        rc = L.wg_regex_to_template(rx, buf, len(buf), C.byref(need))
+    _check(rc)
+    return buf.value.decode("latin-1")
 
 
 class Table:

@@ -343,6 +343,23 @@ int wg_table_add_instances(wg_table_t t, const char *const *templates, const wg_
     }
 }
 
+int wg_regex_to_template(const char *regex, char *out, uint64_t capacity, uint64_t *needed) {
+    if (!regex) return fail(WG_ERR_INVALID, "wg_regex_to_template: regex is null");
+    try {
+        const std::string text = regex_to_template(regex);
+        if (needed) *needed = text.size() + 1;
+        if (!out || capacity < text.size() + 1)
+            return fail(WG_ERR_INVALID, "wg_regex_to_template: the template needs " +
+                                            std::to_string(text.size() + 1) + " bytes");
+        std::memcpy(out, text.c_str(), text.size() + 1);
+        return WG_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(WG_ERR_NOMEM, "wg_regex_to_template: out of host memory");
+    } catch (const std::exception &e) {
+        return fail(WG_ERR_PARSE, e.what());
+    }
+}
+
 uint32_t wg_table_num_instances(wg_table_t t) { return t ? (uint32_t)t->low.table.start.size() : 0; }
 
 uint32_t wg_table_num_states(wg_table_t t) { return t ? (uint32_t)t->low.table.states.size() : 0; }

@@ -58,6 +58,10 @@ class Lowering {
     LoweringState *st_;
 };
 
+// Translates a regular expression into template text in the operator syntax; throws
+// std::runtime_error when the expression has no translation.
+std::string regex_to_template(const char *regex);
+
 void set_last_error(const std::string &msg);
 
 }  // namespace wg

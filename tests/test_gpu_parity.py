@@ -255,6 +255,68 @@ def test_random_trees_every_state_every_token(torch_cuda, restart):
     assert n_states > 400
 
 
+def test_templates_made_from_regular_expressions_run_on_the_device(torch_cuda):
+    """Constraints given as regular expressions: translated on the host, then every state's mask
+    and every (state, token) advance equals the oracle's, and a greedy decode of random logits
+    under the masks produces a string the expression matches."""
+    import itertools
+    import re
+    from wg_synth.vocab import from_tokens
+    import paper_2507_16768_amd as wg
+    torch = torch_cuda
+    alpha = b"01.,[]x"
+    toks = [bytes(t) for n in (1, 2, 3) for t in itertools.product(alpha, repeat=n)]
+    toks.insert(5, b"")                                    # EOS is token 5
+    vocab = from_tokens(toks, eos_id=5)
+    V = vocab.V
+    rxs = [r"\d+(\.\d+)*", r"\[\d+(,\d+)*\]", r"x{1,3}(\.|,)[01]?x"]
+    texts = [wg.regex_to_template(rx) for rx in rxs]
+    ov = O.OracleVocab(vocab.bytes, vocab.offsets, vocab.eos_id)
+    o = O.Oracle(texts, None, ov, restart=False)
+    gv = wg.Vocab(vocab.bytes, vocab.offsets, vocab.eos_id)
+    h = wg.Handle(texts, None, gv, flags=wg.EOS_STOP)
+    st = _all_states(o)
+    d_mask = torch.empty((len(st), h.W), dtype=torch.int32, device="cuda")
+    h.fill_masks(H.dev_states(st), d_mask)
+    assert (H.host_mask(d_mask) == o.fill_masks(st)).all()
+    rep = np.repeat(st, V, axis=0)
+    tk = np.tile(np.arange(V, dtype=np.int32), len(st))
+    d_st = H.dev_states(rep)
+    h.advance(d_st, torch.from_numpy(tk).cuda())
+    assert (H.host_states(d_st) == o.advance(rep, tk)).all()
+    # decode: 64 requests per expression, greedy on seeded logits until every request is FINAL
+    errors_before = h.error_count()                         # from the illegal pairs fed above
+    B = 64 * len(rxs)
+    which = np.arange(B) % len(rxs)
+    d_states = H.dev_states(h.start_states[which])
+    d_mask = torch.empty((B, h.W), dtype=torch.int32, device="cuda")
+    d_tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    outs = [b""] * B
+    done = np.zeros(B, dtype=bool)
+    for k in range(40):
+        x = ws.make_logits(9, B, V, 1.0, tag=k)
+        x[:, 5] += 0.5 * k - 4.0                            # EOS grows more likely with time
+        h.fill_masks(d_states, d_mask)
+        wg.masked_argmax(H.dev_logits(x), d_mask, d_tok)
+        h.advance(d_states, d_tok)
+        t_h, s_h = d_tok.cpu().numpy(), H.host_states(d_states)
+        for b in range(B):
+            if not done[b]:
+                if t_h[b] == 5:
+                    done[b] = True
+                    assert s_h[b, 0] == O.SID_FINAL
+                else:
+                    assert t_h[b] >= 0
+                    outs[b] += toks[t_h[b]]
+        if done.all():
+            break
+    assert done.all()
+    for b in range(B):
+        assert re.fullmatch(rxs[which[b]].encode(), outs[b]), (rxs[which[b]], outs[b])
+    print(sorted(set(outs))[:6], flush=True)
+    assert len(set(outs)) > 20 and h.error_count() == errors_before
+
+
 def test_tiny_shapes_and_no_eos(torch_cuda):
     torch = torch_cuda
     import paper_2507_16768_amd as wg

@@ -115,6 +115,129 @@ def test_instances_appended_one_by_one_give_the_same_table():
         _same_machine(w.texts, w.args, True, lmax=lmax, table=t)
 
 
+def _language_equals_regex(rx, alphabet, max_len, extra=()):
+    """The template made from `rx`, run by the oracle, accepts exactly what Python's re accepts."""
+    import itertools
+    import re
+    text = wg.regex_to_template(rx)
+    o = O.Oracle([text], None, None, restart=False)
+    full = re.compile(rx.encode("latin-1") if isinstance(rx, str) else rx)
+    start = (o.start_state(0), 0)
+    n_acc = 0
+    words = itertools.chain(extra, (bytes(t) for n in range(max_len + 1) for t in itertools.product(alphabet, repeat=n)))
+    for w in words:
+        st = o.walk_bytes(start, w)
+        accepted = st is not None and o.step(st[0], st[1], 256) == (O.SID_FINAL, 0)
+        assert accepted == bool(full.fullmatch(w)), (rx, text, w)
+        n_acc += accepted
+    return text, n_acc
+
+
+@pytest.mark.parametrize("rx,alphabet,max_len,extra", [(c + ((),))[:4] for c in [
+    (r"\d+(\.\d+)*", b"01.x", 8),                      # the paper's worked example
+    (r'"[^"]*"', b'"a\\', 6),
+    (r"ab(cd)?e", b"abcde", 7),
+    (r"a(bc|de)f", b"abcdef", 5),
+    (r"\[\d+(,\d+)*\]", b"[]1,", 8),
+    (r"(ab)+c", b"abc", 8),
+    (r"x{2,4}y", b"xy", 7),
+    (r"[a-c]{1,3}", b"abcd", 5),
+    (r"(ab){1,3}c", b"abc", 8),
+    (r"a(b(c)?)?d", b"abcd", 5),
+    (r"a(bc|d(e)?)f", b"abcdef", 5),
+    (r"x(ab|c\d*)y", b"xabc1y", 6),
+    (r"(a|b|c)d", b"abcd", 3),
+    (r"a?b", b"ab", 4),
+    (r"(ab)*", b"ab", 8),
+    (r"", b"a", 2),
+    (r"^\w+@\w+\.(com|org)$", b"a@.co", 5,
+     (b"a@b.com", b"ab@c.org", b"a_1@b2.org", b"a@b.co", b"a@b.comm", b"@b.com", b"a@b.cog", b"a@@b.com", b"a@b.com.org")),
+    (r"-?\d+", b"-12", 5),
+    (r"\{\"k\":(true|false)\}", b'{}"k:tf', 4,
+     (b'{"k":true}', b'{"k":false}', b'{"k":tru}', b'{"k":truefalse}', b'{"k":true}}', b'{"k":talse}')),
+    (r"(?:\x41|\x42)+\n", b"AB\n", 5),
+    (r"[^\s,]+(,[^\s,]+)*", b"a, b", 7),
+]])
+def test_regex_lowering_matches_the_host_regex_engine(rx, alphabet, max_len, extra):
+    text, n_acc = _language_equals_regex(rx, alphabet, max_len, extra)
+    assert n_acc > 0
+    _same_machine([text], None, False)                  # and the library lowers its own output like the oracle
+
+
+def test_regex_lowering_of_the_worked_example_is_the_listing(golden_dir):
+    """The translation gives the paper's operator tree for its own example: same states, same
+    byte classes, as the listing kept under tests/golden (the listing's redundant allow members
+    aside, which no byte can reach because a wait member wins)."""
+    with open(os.path.join(golden_dir, "worked_example_template.txt")) as f:
+        listing = "".join(l for l in f if not l.startswith("#"))
+    made = wg.Table([wg.regex_to_template(r"\d+(\.\d+)*")])
+    paper = wg.Table([listing])
+    assert made.num_states == paper.num_states == 6
+    for sid in range(6):
+        a, b = made.state(sid), paper.state(sid)
+        assert {k: a[k] for k in ("kind", "next_a", "next_b", "eos_next")} == \
+               {k: b[k] for k in ("kind", "next_a", "next_b", "eos_next")}, sid
+        assert [made.symbol_class(sid, x) for x in range(257)] == [paper.symbol_class(sid, x) for x in range(257)]
+
+
+def test_random_regexes_translate_to_their_own_language_or_are_refused():
+    """Seeded random expressions over a small alphabet: whatever the translation accepts must
+    mean what the host regex engine says it means; the rest must be refused with a parse error."""
+    rng = Counter(77, 5)
+    atoms = ["a", "b", "1", ",", "[ab]", "\\d", "[a1]"]
+
+    def gen(depth):
+        n = rng.between(1, 3)
+        parts = []
+        for _ in range(n):
+            k = rng.between(0, 9)
+            if depth < 2 and k >= 7:
+                inner = gen(depth + 1)
+                if rng.between(0, 2) == 0:
+                    inner += "|" + gen(depth + 1)
+                part = "(" + inner + ")"
+            else:
+                part = atoms[rng.between(0, len(atoms) - 1)]
+            q = rng.between(0, 7)
+            part += {0: "*", 1: "+", 2: "?", 3: "{1,2}"}.get(q, "")
+            parts.append(part)
+        return "".join(parts)
+
+    ok = refused = 0
+    for _ in range(400):
+        rx = gen(0)
+        try:
+            _language_equals_regex(rx, b"ab1,", 6)
+            ok += 1
+        except wg.WgError as e:
+            assert e.code == -2 and "regex" in str(e), rx
+            refused += 1
+    assert ok >= 60 and refused >= 60, (ok, refused)
+
+
+@pytest.mark.parametrize("rx,frag", [
+    (r"a*b*", "two repeated classes"),
+    (r"(ab|cd|ef)", "three-way"),
+    (r"(a|ab)", "same byte"),
+    (r"(a*b)*c", "start with a single byte"),
+    (r"a*a", "also matches"),
+    (r"(a(bc)*)*d", "end of a repeated group"),
+    (r"(ab)?(cd)?e", "followed by a single byte"),
+    (r"(", "unbalanced"),
+    (r"a{3,2}", "reversed"),
+    (r"a+?", "lazy"),
+    (r"\1", "back-references"),
+    (r"[z-a]", "reversed range"),
+    (r"*a", "nothing to repeat"),
+    (r"a{2000}", "above 1000"),
+    (r"[^\x00-\xff]", "no byte"),
+])
+def test_regex_lowering_refuses_what_the_operators_cannot_express(rx, frag):
+    with pytest.raises(wg.WgError) as e:
+        wg.regex_to_template(rx)
+    assert e.value.code == -2 and frag in str(e.value), str(e.value)
+
+
 @pytest.mark.parametrize("text,frag", [
     ("IfElse(condition=Wait(allow={a}, true_waits={x}, false_waits={x}), if_body=None, else_body=None)", "overlap"),
     ("Sequence(Wait(allow={a}, wait={<eos>}), Write(\"b\"))", "follow"),
