@@ -227,6 +227,18 @@ int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uin
 int wg_advance_fill_masks(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B,
                           uint32_t *d_bitmask, void *stream);
 
+/* wg_decode_step: the whole per-step path in one call, for the decode loop: the states are
+ * advanced by the tokens sampled in the step before (d_tokens == NULL skips this: first step),
+ * the masks of the new states are produced into d_bitmask as by wg_fill_masks and applied to
+ * d_logits ([B][V] with V of the handle's vocabulary, layout as in wg_apply_mask) as by
+ * wg_apply_mask.  Same results as wg_advance + wg_fill_masks + wg_apply_mask in four kernel
+ * launches instead of six: the advance rides in the lookup kernel and the masking in the gather
+ * kernel (rows whose address or stride rules out 16-byte stores are masked by the separate
+ * apply kernels instead).  In wg_profile_read the combined kernels count as lookup and gather. */
+int wg_decode_step(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B,
+                   uint32_t *d_bitmask, void *d_logits, wg_dtype_t dtype, int64_t row_stride_elems,
+                   void *stream);
+
 /* Forget every cached mask row and every class-table index built from the operators' allow /
  * wait sets.  O(1) and launches nothing: the handle's cache generation is bumped on the host
  * and travels with every later call as a kernel argument (so a clear recorded into a HIP

@@ -57,6 +57,7 @@ EXPORTS = [
     "wg_last_error", "wg_select_tokens", "wg_profile_enable", "wg_profile_read", "wg_masked_argmax",
     "wg_add_instances", "wg_num_instances", "wg_cache_resize", "wg_table_add_instances",
     "wg_table_num_instances", "wg_advance_fill_masks", "wg_regex_to_template",
+    "wg_decode_step",
 ]
 
 
@@ -107,6 +108,7 @@ def load_library():
     L.wg_apply_mask.argtypes = [vp, C.c_int, u32, u32, i64, vp, vp]
     L.wg_advance.argtypes = [vp, vp, vp, u32, vp]
     L.wg_advance_fill_masks.argtypes = [vp, vp, vp, u32, vp, vp]
+    L.wg_decode_step.argtypes = [vp, vp, vp, u32, vp, vp, C.c_int, i64, vp]
     L.wg_masked_argmax.argtypes = [vp, C.c_int, u32, u32, i64, vp, vp, vp]
     L.wg_cache_clear.argtypes = [vp, vp]
     L.wg_cache_stats.argtypes = [vp, C.POINTER(_Stats)]
@@ -275,6 +277,27 @@ class Handle:
         _check(load_library().wg_advance_fill_masks(
             self._h, _dev(states, torch.int32, "states"), _dev(tokens, torch.int32, "tokens"), B,
             _dev(bitmask, torch.int32, "bitmask"), _stream_ptr(stream)))
+
+    def decode_step(self, states, tokens, bitmask, logits, stream=None):
+        """wg_decode_step; tokens may be None (first step)."""
+        import torch
+        B = states.shape[0]
+        if tuple(states.shape) != (B, 2) or tuple(bitmask.shape) != (B, self.W):
+            raise ValueError("states must be [B, 2] and bitmask [B, W]")
+        if tokens is not None and tuple(tokens.shape) != (B,):
+            raise ValueError("tokens must be [B]")
+        if logits.dim() != 2 or not logits.is_cuda or logits.stride(1) != 1 or logits.shape[0] != B:
+            raise ValueError("logits must be a [B, V] device tensor with unit inner stride")
+        if logits.shape[1] != self.vocab.V:
+            raise ValueError("logits must have the vocabulary's width")
+        dt = {torch.float32: F32, torch.bfloat16: BF16}.get(logits.dtype)
+        if dt is None:
+            raise ValueError("logits must be float32 or bfloat16")
+        _check(load_library().wg_decode_step(
+            self._h, _dev(states, torch.int32, "states"),
+            None if tokens is None else _dev(tokens, torch.int32, "tokens"), B,
+            _dev(bitmask, torch.int32, "bitmask"), C.c_void_p(logits.data_ptr()), dt, logits.stride(0),
+            _stream_ptr(stream)))
 
     def add_instances(self, texts, args, stream=None):
         """wg_add_instances: returns the start states [n, 2] of the new instances."""

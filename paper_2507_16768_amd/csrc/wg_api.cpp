@@ -505,15 +505,15 @@ uint32_t wg_mask_words(wg_handle_t h) { return h ? h->vocab->dv.W : 0; }
 
 namespace {
 int fill(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B, uint32_t *d_bitmask,
-         void *stream, const char *who) {
+         void *stream, const char *who, void *d_logits = nullptr, int dtype = WG_F32, int64_t logits_stride = 0) {
     if (B == 0) return fail(WG_ERR_INVALID, std::string(who) + ": B is 0");
     if (B > kMaxBatch) return fail(WG_ERR_INVALID, std::string(who) + ": B above 65535");
     int rc = ensure_batch(h, B);
     if (rc != WG_OK) return rc;
     hipEvent_t ev[8];
     if (h->profiling) for (auto &e : ev) { e = take_event(h); h->fill_events.push_back(e); }
-    WG_HIP(launch_fill(h->dt, h->vocab->dv, h->dc, d_states, d_tokens, B, d_bitmask, h->n_cu,
-                       static_cast<hipStream_t>(stream), h->profiling ? ev : nullptr));
+    WG_HIP(launch_fill(h->dt, h->vocab->dv, h->dc, d_states, d_tokens, B, d_bitmask, d_logits, dtype,
+                       logits_stride, h->n_cu, static_cast<hipStream_t>(stream), h->profiling ? ev : nullptr));
     return WG_OK;
 }
 }  // namespace
@@ -530,6 +530,15 @@ int wg_advance_fill_masks(wg_handle_t h, wg_state_t *d_states, const int32_t *d_
     if (!h || !d_states || !d_tokens || !d_bitmask)
         return fail(WG_ERR_INVALID, "wg_advance_fill_masks: null argument");
     return fill(h, d_states, d_tokens, B, d_bitmask, stream, "wg_advance_fill_masks");
+}
+
+int wg_decode_step(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B,
+                   uint32_t *d_bitmask, void *d_logits, wg_dtype_t dtype, int64_t row_stride_elems,
+                   void *stream) {
+    if (!h || !d_states || !d_bitmask || !d_logits) return fail(WG_ERR_INVALID, "wg_decode_step: null argument");
+    if (dtype != WG_F32 && dtype != WG_BF16) return fail(WG_ERR_INVALID, "wg_decode_step: unknown dtype");
+    if (row_stride_elems < (int64_t)h->vocab->dv.V) return fail(WG_ERR_INVALID, "wg_decode_step: row stride smaller than V");
+    return fill(h, d_states, d_tokens, B, d_bitmask, stream, "wg_decode_step", d_logits, dtype, row_stride_elems);
 }
 
 int wg_apply_mask(void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V, int64_t row_stride_elems,

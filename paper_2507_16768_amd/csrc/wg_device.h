@@ -107,9 +107,12 @@ struct DeviceCache {
 };
 
 // ev, when not null, holds eight events: a begin / end pair for each of the four kernels of a fill.
-// With tokens != nullptr the states are first advanced by them (in place, in the lookup kernel).
+// With tokens != nullptr the states are first advanced by them (in place, in the lookup kernel);
+// with logits != nullptr the mask is also applied to them (in the gather kernel when their
+// layout allows 16-byte stores).
 hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
                        wg_state_t *states, const int32_t *tokens, uint32_t B, uint32_t *bitmask,
+                       void *logits, int dtype, int64_t logits_stride,
                        uint32_t n_cu, hipStream_t s, hipEvent_t *ev);
 hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
                         const uint32_t *bitmask, hipStream_t s);

@@ -545,33 +545,44 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
 // gather: bitmask[b] <- the row of request b's key (zeros without a key): from the arena, or
 // from the bitmask row of the request that built it when the row could not be kept.  Rows are
 // copied 16 bytes per thread when the caller's row stride allows it.
+// The miss lists have been consumed by the kernels that ran before the last kernel of a fill:
+// one thread of it counts their rows as used and empties them for the next call.
+__device__ __forceinline__ void close_fill(const DeviceCache &Cc)
+{
+    const unsigned long long sc = Cc.ctr->slot_ctr;
+    const uint32_t used = (uint32_t)(sc >> 32) == Cc.epoch ? (uint32_t)sc : 0u;
+    const uint32_t room = Cc.cap_rows - used, n = Cc.ctr->n_miss;
+    if (n > room) Cc.ctr->uncached_builds += n - room;
+    Cc.ctr->slot_ctr = ((unsigned long long)Cc.epoch << 32) | (used + (n < room ? n : room));
+    Cc.ctr->n_miss = 0; Cc.ctr->n_class_miss = 0;
+    Cc.ctr->launch++;
+}
+
+// Where the mask of request b is: a row of the arena, the bitmask row of the request that
+// built it uncached (possibly b's own: then `in_place`), or nowhere (nullptr: a row of zeros).
+__device__ __forceinline__ const uint32_t *mask_source(const DeviceCache &Cc, uint32_t b, uint32_t B, uint32_t W,
+                                                       const uint32_t *bitmask, bool &in_place)
+{
+    in_place = false;
+    const uint32_t ref = Cc.row_ref[b];
+    if (ref < kRefByKey) return ref < Cc.cap_rows ? Cc.arena + (size_t)ref * Cc.row_stride : nullptr;   // cached before this call
+    if (ref == kNoKey) return nullptr;
+    const unsigned long long t = Cc.tags[ref & ~kRefByKey];
+    if ((uint32_t)(t >> 32) == Cc.epoch) return Cc.arena + (size_t)(uint32_t)t * Cc.row_stride;
+    const uint32_t req = (uint32_t)(t & 0xFFFFu);
+    if (req == b) { in_place = true; return bitmask + (size_t)b * W; }          // built in place by key_build
+    return req < B ? bitmask + (size_t)req * W : nullptr;                        // built for another request of this call
+}
+
 template <bool kVec>
 __global__ void __launch_bounds__(256)
 gather_kernel(DeviceCache Cc, uint32_t W, uint32_t *__restrict__ bitmask)
 {
     const uint32_t b = blockIdx.y;
-    // The miss lists have been consumed by the kernels that ran before this one: count their
-    // rows as used and empty them for the next call.
-    if (blockIdx.x == 0 && b == 0 && threadIdx.x == 0) {
-        const unsigned long long sc = Cc.ctr->slot_ctr;
-        const uint32_t used = (uint32_t)(sc >> 32) == Cc.epoch ? (uint32_t)sc : 0u;
-        const uint32_t room = Cc.cap_rows - used, n = Cc.ctr->n_miss;
-        if (n > room) Cc.ctr->uncached_builds += n - room;
-        Cc.ctr->slot_ctr = ((unsigned long long)Cc.epoch << 32) | (used + (n < room ? n : room));
-        Cc.ctr->n_miss = 0; Cc.ctr->n_class_miss = 0;
-        Cc.ctr->launch++;
-    }
-    const uint32_t ref = Cc.row_ref[b];
-    const uint32_t *src = nullptr;
-    if (ref < kRefByKey) {
-        if (ref < Cc.cap_rows) src = Cc.arena + (size_t)ref * Cc.row_stride;   // cached before this call
-    } else if (ref != kNoKey) {
-        const unsigned long long t = Cc.tags[ref & ~kRefByKey];
-        if ((uint32_t)(t >> 32) == Cc.epoch) src = Cc.arena + (size_t)(uint32_t)t * Cc.row_stride;
-        else if ((uint32_t)(t & 0xFFFFu) == b) return;    // built in place by key_build
-        else if ((uint32_t)(t & 0xFFFFu) < gridDim.y)
-            src = bitmask + (size_t)(t & 0xFFFFu) * W;    // built for another request of this call
-    }
+    if (blockIdx.x == 0 && b == 0 && threadIdx.x == 0) close_fill(Cc);
+    bool in_place;
+    const uint32_t *src = mask_source(Cc, b, gridDim.y, W, bitmask, in_place);
+    if (in_place) return;
     uint32_t *dst = bitmask + (size_t)b * W;
     if (kVec) {
         const uint4 *s4 = reinterpret_cast<const uint4 *>(src);
@@ -585,33 +596,90 @@ gather_kernel(DeviceCache Cc, uint32_t W, uint32_t *__restrict__ bitmask)
 }
 
 // ---------------------------------------------------------------------------------------------
-// apply: thread = 8 consecutive tokens = one mask byte.  Nothing is read from the logits:
+// apply: a thread takes mask bytes (8 consecutive tokens each) 256 apart, all loaded before any
+// is used.  Nothing is read from the logits:
 // a fully allowed group is skipped, a group with no allowed token is overwritten with one
 // 16-byte store per 8 bf16 (two for fp32), and a mixed group stores -inf element by element,
 // one store per disallowed token (found by count-trailing-zeros, so a group inside a
 // free-text Wait, which has one or two such tokens, issues one or two stores).
+constexpr uint32_t kApplyGroups = 2;       // mask bytes per thread, 256 apart
 template <typename Vec, int kVecs, typename Elem>
 __global__ void __launch_bounds__(256)
 apply_vec_kernel(Elem *__restrict__ logits, int64_t row_stride, uint32_t V, uint32_t W,
                  const uint32_t *__restrict__ bitmask, Elem ninf)
 {
     const uint32_t b = blockIdx.y;
-    const uint32_t g = blockIdx.x * blockDim.x + threadIdx.x;      // group of 8 tokens
-    if (g * 8u >= V) return;
-    const uint32_t m = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * W)[g];
-    if (m == 0xFFu) return;
-    Elem *p = logits + (int64_t)b * row_stride + (int64_t)g * 8;
-    uint32_t z = ~m & 0xFFu;                                        // disallowed positions
-    if (z == 0xFFu) {
-        union { Vec v[kVecs]; Elem e[8]; } u;
+    const uint32_t g0 = blockIdx.x * (256u * kApplyGroups) + threadIdx.x;   // group of 8 tokens
+    const uint8_t *row = reinterpret_cast<const uint8_t *>(bitmask + (size_t)b * W);
+    uint32_t m[kApplyGroups];
 #pragma unroll
-        for (int i = 0; i < 8; i++) u.e[i] = ninf;
-        Vec *pv = reinterpret_cast<Vec *>(p);
-#pragma unroll
-        for (int i = 0; i < kVecs; i++) pv[i] = u.v[i];
-        return;
+    for (uint32_t i = 0; i < kApplyGroups; i++) {
+        const uint32_t g = g0 + i * 256u;
+        m[i] = g * 8u < V ? row[g] : 0xFFu;
     }
-    while (z) { p[__builtin_ctz(z)] = ninf; z &= z - 1u; }
+#pragma unroll
+    for (uint32_t i = 0; i < kApplyGroups; i++) {
+        if (m[i] == 0xFFu) continue;
+        Elem *p = logits + (int64_t)b * row_stride + (int64_t)(g0 + i * 256u) * 8;
+        uint32_t z = ~m[i] & 0xFFu;                                 // disallowed positions
+        if (z == 0xFFu) {
+            union { Vec v[kVecs]; Elem e[8]; } u;
+#pragma unroll
+            for (int k = 0; k < 8; k++) u.e[k] = ninf;
+            Vec *pv = reinterpret_cast<Vec *>(p);
+#pragma unroll
+            for (int k = 0; k < kVecs; k++) pv[k] = u.v[k];
+        } else {
+            while (z) { p[__builtin_ctz(z)] = ninf; z &= z - 1u; }
+        }
+    }
+}
+
+// gather and apply in one pass, the last kernel of a whole decode step: thread = one mask byte
+// = 8 tokens, as in apply; the byte comes from where the request's mask lives, goes to the
+// caller's bitmask row, and its disallowed tokens are stored as -inf.
+constexpr uint32_t kGaGroups = 4;          // mask bytes per thread of gather_apply, 256 apart
+template <typename Vec, int kVecs, typename Elem>
+__global__ void __launch_bounds__(256)
+gather_apply_kernel(DeviceCache Cc, Elem *__restrict__ logits, int64_t row_stride, uint32_t V, uint32_t W,
+                    uint32_t *__restrict__ bitmask, Elem ninf)
+{
+    const uint32_t b = blockIdx.y;
+    bool in_place;
+    const uint32_t *src = mask_source(Cc, b, gridDim.y, W, bitmask, in_place);
+    const uint32_t g0 = blockIdx.x * (256u * kGaGroups) + threadIdx.x;      // group of 8 tokens
+    uint32_t m[kGaGroups];
+#pragma unroll
+    for (uint32_t i = 0; i < kGaGroups; i++) {
+        const uint32_t g = g0 + i * 256u;
+        m[i] = (src && g < 4u * W) ? reinterpret_cast<const uint8_t *>(src)[g] : 0u;
+    }
+    if (!in_place) {
+        uint8_t *dst = reinterpret_cast<uint8_t *>(bitmask + (size_t)b * W);
+#pragma unroll
+        for (uint32_t i = 0; i < kGaGroups; i++) {
+            const uint32_t g = g0 + i * 256u;
+            if (g < 4u * W) dst[g] = (uint8_t)m[i];
+        }
+    }
+#pragma unroll
+    for (uint32_t i = 0; i < kGaGroups; i++) {
+        const uint32_t g = g0 + i * 256u;
+        if (g * 8u >= V || m[i] == 0xFFu) continue;
+        Elem *p = logits + (int64_t)b * row_stride + (int64_t)g * 8;
+        uint32_t z = ~m[i] & 0xFFu;                                 // disallowed positions
+        if (z == 0xFFu) {
+            union { Vec v[kVecs]; Elem e[8]; } u;
+#pragma unroll
+            for (int k = 0; k < 8; k++) u.e[k] = ninf;
+            Vec *pv = reinterpret_cast<Vec *>(p);
+#pragma unroll
+            for (int k = 0; k < kVecs; k++) pv[k] = u.v[k];
+        } else {
+            while (z) { p[__builtin_ctz(z)] = ninf; z &= z - 1u; }
+        }
+    }
+    if (blockIdx.x == 0 && b == 0 && threadIdx.x == 0) close_fill(Cc);
 }
 
 // masked argmax: a row is split over several workgroups; a thread takes 32-token groups (one mask word and up
@@ -869,8 +937,15 @@ static inline void launch(K kernel, dim3 grid, dim3 block, uint32_t lds, hipStre
     else hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
 }
 
+static bool apply_vec_ok(const void *logits, int dtype, uint32_t V, int64_t row_stride)
+{
+    const size_t esz = dtype == WG_F32 ? 4 : 2;
+    return reinterpret_cast<uintptr_t>(logits) % 16 == 0 && (row_stride * (int64_t)esz) % 16 == 0 && V % 8u == 0;
+}
+
 hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
                        wg_state_t *states, const int32_t *tokens, uint32_t B, uint32_t *bitmask,
+                       void *logits, int dtype, int64_t logits_stride,
                        uint32_t n_cu, hipStream_t s, hipEvent_t *ev)
 {
     if (tokens) launch(advance_lookup_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s, ev, T, Vc, Cc, states, tokens, B);
@@ -885,9 +960,22 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
     uint32_t kb = n_cu * 2u;
     launch(key_build_kernel, dim3(B < kb ? B : kb), dim3(1024), Cc.row_stride * 4u, s,
            ev ? ev + 4 : nullptr, T, Vc, Cc, bitmask);
+    hipEvent_t *ge = ev ? ev + 6 : nullptr;
+    if (logits && apply_vec_ok(logits, dtype, Vc.V, logits_stride)) {
+        const dim3 g(cdiv(4u * Vc.W, 256 * kGaGroups), B);
+        if (dtype == WG_F32)
+            launch(gather_apply_kernel<uint4, 2, uint32_t>, g, dim3(256), 0, s, ge, Cc, (uint32_t *)logits,
+                   logits_stride, Vc.V, Vc.W, bitmask, 0xFF800000u);
+        else
+            launch(gather_apply_kernel<uint4, 1, uint16_t>, g, dim3(256), 0, s, ge, Cc, (uint16_t *)logits,
+                   logits_stride, Vc.V, Vc.W, bitmask, (uint16_t)0xFF80u);
+        return hipGetLastError();
+    }
     const bool vec = Vc.W % 4u == 0 && reinterpret_cast<uintptr_t>(bitmask) % 16 == 0;
-    if (vec) launch(gather_kernel<true>, dim3(cdiv(Vc.W / 4u, 256), B), dim3(256), 0, s, ev ? ev + 6 : nullptr, Cc, Vc.W, bitmask);
-    else launch(gather_kernel<false>, dim3(cdiv(Vc.W, 256 * 4), B), dim3(256), 0, s, ev ? ev + 6 : nullptr, Cc, Vc.W, bitmask);
+    if (vec) launch(gather_kernel<true>, dim3(cdiv(Vc.W / 4u, 256), B), dim3(256), 0, s, ge, Cc, Vc.W, bitmask);
+    else launch(gather_kernel<false>, dim3(cdiv(Vc.W, 256 * 4), B), dim3(256), 0, s, ge, Cc, Vc.W, bitmask);
+    // logits that do not allow 16-byte stores take the separate apply kernels
+    if (logits) return launch_apply(logits, dtype, B, Vc.V, logits_stride, bitmask, s);
     return hipGetLastError();
 }
 
@@ -895,11 +983,9 @@ hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t
                         const uint32_t *bitmask, hipStream_t s)
 {
     uint32_t W = (V + 31u) / 32u;
-    size_t esz = dtype == WG_F32 ? 4 : 2;
-    bool vec_ok = (reinterpret_cast<uintptr_t>(logits) % 16 == 0) && ((row_stride * (int64_t)esz) % 16 == 0) &&
-                  (V % 8u == 0);
+    const bool vec_ok = apply_vec_ok(logits, dtype, V, row_stride);
     if (vec_ok) {
-        dim3 g(cdiv(V / 8u, 256), B);
+        dim3 g(cdiv(V / 8u, 256 * kApplyGroups), B);
         if (dtype == WG_F32)
             apply_vec_kernel<uint4, 2, uint32_t><<<g, 256, 0, s>>>((uint32_t *)logits, row_stride, V, W, bitmask, 0xFF800000u);
         else

@@ -139,6 +139,55 @@ def test_fused_advance_and_fill_match_the_separate_calls(torch_cuda, idx, V, B, 
     assert h.error_count() == 1
 
 
+@pytest.mark.parametrize("idx,V,B,steps,rows,pad", [
+    (3, 3001, 8, 40, 0, 0),        # V % 8 != 0: the separate apply kernels do the masking
+    (4, 6008, 24, 40, 0, 0),       # bf16, 16-byte stores: masking inside the gather kernel
+    (4, 6008, 24, 24, 0, 8),       # ... with padded logits rows
+    (4, 6008, 24, 24, 0, 3),       # ... with a row stride that rules out 16-byte stores
+    (5, 4104, 96, 24, 5, 0),       # five cache rows: most masks are built straight into the bitmask
+    (2, 4096, 6, 30, 0, 0),
+])
+def test_decode_step_matches_the_oracle(torch_cuda, idx, V, B, steps, rows, pad):
+    """wg_decode_step (advance + fill + apply in one call) against the oracle on every step:
+    states, full bitmask and masked logits."""
+    torch = torch_cuda
+    w = ws.make_workload(idx, V=V, B=B, steps=steps)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    if rows:
+        h.cache_resize(rows)
+    cur = H.start_states(o, w)
+    toks, sts, _ = o.trajectory(cur, w.token_draws(steps))
+    d_states = H.dev_states(cur)
+    d_mask = torch.empty((B, h.W), dtype=torch.int32, device="cuda")
+    prev = None
+    for k in range(steps):
+        print("decode_step cfg%d step %d" % (idx, k), flush=True) if k % 8 == 0 else None
+        host = H.logits_for(w, tag=k)
+        d_log = H.dev_logits(host)
+        if pad:
+            buf = torch.zeros((B, V + pad), dtype=d_log.dtype, device="cuda")
+            buf[:, :V] = d_log
+            d_log = buf[:, :V]
+        d_mask.fill_(0x77777777)
+        h.decode_step(d_states, prev, d_mask, d_log)
+        assert (H.host_states(d_states) == cur).all(), k
+        want_mask = o.fill_masks(cur)
+        assert (H.host_mask(d_mask) == want_mask).all(), k
+        want = O.apply_mask(host.copy(), want_mask)
+        want_bits = want.view(np.uint32) if want.dtype == np.float32 else want
+        assert (H.host_logit_bits(d_log.contiguous()) == want_bits).all(), k
+        if pad:
+            assert (H.host_logit_bits(buf[:, V:].contiguous()) == 0).all()
+        prev = torch.from_numpy(toks[k]).cuda()
+        cur = sts[k]
+    h.advance(d_states, prev)
+    assert (H.host_states(d_states) == cur).all()
+    s = h.cache_stats()
+    assert s["lookups"] == steps * B and h.error_count() == 0
+    assert (s["uncached_builds"] > 0) == bool(rows)
+
+
 def test_long_tokens_take_the_generic_paths(torch_cuda):
     """Tokens of up to 40 bytes: longer than the three 8-byte chunks the fast paths hold."""
     import dataclasses
@@ -649,5 +698,11 @@ def test_argument_errors_on_device_calls(torch_cuda):
     assert L.wg_apply_mask(C.c_void_p(16), 0, 1, 32, 16, C.c_void_p(16), None) == -1
     assert L.wg_advance(None, None, None, 1, None) == -1
     assert b"null" in L.wg_last_error()
+    assert L.wg_decode_step(h._h, C.c_void_p(16), None, 1, C.c_void_p(16), None, 0, 2000, None) == -1
+    assert L.wg_decode_step(h._h, C.c_void_p(16), None, 1, C.c_void_p(16), C.c_void_p(16), 5, 2000, None) == -1
+    assert L.wg_decode_step(h._h, C.c_void_p(16), None, 1, C.c_void_p(16), C.c_void_p(16), 0, 1999, None) == -1
+    assert L.wg_decode_step(h._h, C.c_void_p(16), None, 0, C.c_void_p(16), C.c_void_p(16), 0, 2000, None) == -1
+    assert L.wg_advance_fill_masks(h._h, C.c_void_p(16), None, 1, C.c_void_p(16), None) == -1
+    assert L.wg_cache_resize(h._h, 0) == -1
     with pytest.raises(wg.WgError):
         wg.Vocab(np.zeros(4, np.uint8), np.array([0, 3, 2], np.uint64), 0)
