@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # WRITE_SIZE (profiles/bench_config4_hbm_traffic.txt; fetch scaled x2.000, write x1.000 by
 # the counters of a 512 MiB device copy).  They describe the kernels whose source hashes to
 # TRAFFIC_SOURCE_SHA256; with any other kernel source the field is reported as null.
-TRAFFIC_BYTES = {"class_scan": 3.86e6, "key_build": 9.02e6, "gather": 9.93e6, "apply": 58.76e6}
-TRAFFIC_SOURCE_SHA256 = "96f8b977ca626b7c8061d964a877d0ca45980b57978eae8a77903f1d8b73a546"
+TRAFFIC_BYTES = {"class_scan": 3.87e6, "key_build": 9.04e6, "gather": 10.09e6, "apply": 57.71e6}
+TRAFFIC_SOURCE_SHA256 = "dc347c227d4d4e290cdb95511b3ae01976c2998e0d460d6fa0b3750f82e423e9"
 
 
 def kernel_source_sha256():
@@ -251,6 +251,23 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / K
 
+    # ---- the whole step in one call: advance + fill + apply ----
+    def timed_single(cold):
+        def go(lo, hi):
+            for k in range(lo, hi):
+                if cold:
+                    h.cache_clear()
+                h.decode_step(states, tokens[k - 1] if k else None, mask, ring[k & 3])
+        states.copy_(start)
+        if cold:
+            h.cache_clear()
+        go(0, Wm)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        go(Wm, total)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / K
+
     # Warm first: every key was cached by the pre-pass.  The warm step is short enough for host
     # launch jitter to show, so it is the best of three timed passes (the cold headline below is
     # a single pass).
@@ -260,6 +277,7 @@ def main():
     assert h.cache_stats()["builds"] == pre["builds"], "a warm pass built a mask"
     # (the fused loop also fills for the state after the last step, which no pass before it saw)
     sec_fused_warm = min(timed_fused(False) for _ in range(3))
+    sec_single_warm = min(timed_single(False) for _ in range(3))
     s0 = h.cache_stats()
     sec_cold = timed(True)
     s1 = h.cache_stats()
@@ -269,6 +287,7 @@ def main():
     kt_cold = kernel_times(True)
     spread_cold = step_spread(True)
     sec_fused_cold = timed_fused(True)
+    sec_single_cold = timed_single(True)
     # apply is a single kernel outside the handle: time a back-to-back run of it
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -369,6 +388,10 @@ def main():
         "step_spread": {"note": "per-step times between events recorded at the step boundaries "
                                 "(fill + apply + advance, event cost included)",
                         "cold": spread_cold, "warm": spread_warm},
+        "single_call_step": {"note": "the same steps through wg_decode_step (advance + fill + apply, four launches)",
+                             "cold_ms_per_step": sec_single_cold * 1e3, "warm_ms_per_step": sec_single_warm * 1e3,
+                             "cold_request_steps_per_s": B / sec_single_cold,
+                             "warm_request_steps_per_s": B / sec_single_warm},
         "fused_advance_fill": {"note": "the same steps through wg_apply_mask + wg_advance_fill_masks",
                                "cold_ms_per_step": sec_fused_cold * 1e3, "warm_ms_per_step": sec_fused_warm * 1e3,
                                "cold_request_steps_per_s": B / sec_fused_cold,
