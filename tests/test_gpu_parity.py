@@ -188,6 +188,55 @@ def test_decode_step_matches_the_oracle(torch_cuda, idx, V, B, steps, rows, pad)
     assert (s["uncached_builds"] > 0) == bool(rows)
 
 
+def test_decode_step_replayed_from_a_hip_graph(torch_cuda):
+    """A decode step recorded once into a HIP graph and replayed for every later step, with the
+    program's own eager copies and synchronisations between the replays: every replay (cache
+    misses in the early ones, hits later) must give the oracle's states, masks and logits.  The
+    step path launches kernels only (no allocation, no memset), and the number of the fill call,
+    which tags claimed keys, lives in device memory, so a replay is a new call."""
+    torch = torch_cuda
+    w = ws.make_workload(4, V=6008, B=24, steps=20)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    B, V, steps = w.B, w.vocab.V, w.steps
+    cur = H.start_states(o, w)
+    toks, sts, _ = o.trajectory(cur, w.token_draws(steps))
+    d_states = H.dev_states(cur)
+    d_mask = torch.empty((B, h.W), dtype=torch.int32, device="cuda")
+    d_log = H.dev_logits(H.logits_for(w, tag=0)).clone()
+    d_tok = torch.zeros(B, dtype=torch.int32, device="cuda")
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+
+    def check(k, host):
+        assert (H.host_states(d_states) == cur).all(), k
+        want_mask = o.fill_masks(cur)
+        assert (H.host_mask(d_mask) == want_mask).all(), k
+        assert (H.host_logit_bits(d_log) == O.apply_mask(host.copy(), want_mask)).all(), k
+
+    # step 0 eagerly (no token yet); it also sizes the handle's per-call lists
+    host = H.logits_for(w, tag=0)
+    h.decode_step(d_states, None, d_mask, d_log)
+    check(0, host)
+    torch.cuda.synchronize()
+    # record step 1 .. on a side stream: the recording itself runs nothing
+    with torch.cuda.graph(graph, stream=side):
+        h.decode_step(d_states, d_tok, d_mask, d_log, stream=side)
+    for k in range(1, steps):
+        print("graph replay for step %d" % k, flush=True) if k % 4 == 1 else None
+        d_tok.copy_(torch.from_numpy(toks[k - 1]).cuda())
+        cur = sts[k - 1]
+        host = H.logits_for(w, tag=k)
+        d_log.copy_(H.dev_logits(host))
+        d_mask.fill_(0x11111111)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        check(k, host)
+    s = h.cache_stats()
+    assert s["lookups"] == steps * B and s["builds"] == s["rows_in_use"] > 0 and h.error_count() == 0
+
+
 def test_long_tokens_take_the_generic_paths(torch_cuda):
     """Tokens of up to 40 bytes: longer than the three 8-byte chunks the fast paths hold."""
     import dataclasses
