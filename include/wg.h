@@ -173,7 +173,8 @@ void wg_destroy(wg_handle_t h);
  * The new table slices are copied on `stream`, which is synchronised before the call returns;
  * when the tables outgrow the room reserved for them (half again of what was needed at the
  * last growth) the whole device is synchronised once and the tables move.  On WG_ERR_PARSE
- * nothing was added.  Not to be called while another thread enqueues work on the handle. */
+ * nothing was added; on WG_ERR_NOMEM / WG_ERR_HIP the instances are in the host table but their
+ * states are out of range for the device (all-zero masks) until a later call succeeds.  Not to be called while another thread enqueues work on the handle. */
 int wg_add_instances(wg_handle_t h, const char *const *templates, const wg_args_t *args,
                      uint32_t n_templates, wg_state_t *start_states_out, void *stream);
 uint32_t wg_num_instances(wg_handle_t h);

@@ -146,12 +146,15 @@ def test_fused_advance_and_fill_match_the_separate_calls(torch_cuda, idx, V, B, 
     (4, 6008, 24, 24, 0, 3),       # ... with a row stride that rules out 16-byte stores
     (5, 4104, 96, 24, 5, 0),       # five cache rows: most masks are built straight into the bitmask
     (2, 4096, 6, 30, 0, 0),
+    (4, None, None, 6, 0, 0),      # full size: B=256, V=151,936, the shape the benchmark times
+    (5, None, None, 3, 0, 0),      # full size: B=1,024
 ])
 def test_decode_step_matches_the_oracle(torch_cuda, idx, V, B, steps, rows, pad):
     """wg_decode_step (advance + fill + apply in one call) against the oracle on every step:
     states, full bitmask and masked logits."""
     torch = torch_cuda
-    w = ws.make_workload(idx, V=V, B=B, steps=steps)
+    w = ws.make_workload(idx, V=V, B=B, steps=steps) if V else ws.make_workload(idx, steps=steps)
+    V, B = w.vocab.V, w.B
     o = H.make_oracle(w)
     v, h = H.make_gpu(w)
     if rows:
