@@ -138,8 +138,21 @@ def main():
 
     t0 = time.perf_counter()
     vocab = wg.Vocab(w.vocab.bytes, w.vocab.offsets, w.vocab.eos_id)
+    vocab_ms = (time.perf_counter() - t0) * 1e3
+    t0 = time.perf_counter()
     h = wg.Handle(w.texts, w.args, vocab, flags=wg.EOS_RESTART)
     compile_ms = (time.perf_counter() - t0) * 1e3
+    # a request joining a running engine: one instance added to a live handle (host lowering of
+    # its arguments into the cached static structure, upload of the new table slices)
+    n_join = min(64, len(w.texts) - 1)
+    join_us = []
+    if n_join > 0:
+        hj = wg.Handle(w.texts[:1], w.args[:1] if w.args else None, vocab, flags=wg.EOS_RESTART)
+        for i in range(1, n_join + 1):
+            t0 = time.perf_counter()
+            hj.add_instances(w.texts[i:i + 1], w.args[i:i + 1] if w.args else None)
+            join_us.append((time.perf_counter() - t0) * 1e6)
+        del hj
     W = h.W
     start = torch.from_numpy(np.ascontiguousarray(h.start_states[w.request_template]).view(np.int32).copy()).cuda()
 
@@ -433,7 +446,10 @@ def main():
                    "cold_request_steps_per_s": B / sec_greedy_cold, "warm_request_steps_per_s": B / sec_greedy_warm,
                    "masked_argmax_us": argmax_us,
                    "masked_argmax_dense_read_GBs": B * (row_bytes + esz * V) / (argmax_us * 1e-6) / 1e9},
-        "compile_ms": compile_ms,
+        "host_setup": {"vocabulary_indexes_ms": vocab_ms, "compile_all_instances_ms": compile_ms,
+                       "instances": len(w.texts),
+                       "add_one_instance_us_median": float(np.median(join_us)) if join_us else None,
+                       "add_one_instance_us_p90": float(np.percentile(join_us, 90)) if join_us else None},
         "prepass": {"builds": pre["builds"], "lookups": pre["lookups"], "class_scans": pre["class_scans"]},
     }
     if cpu is not None:
