@@ -29,8 +29,12 @@
  *   - Every function returns WG_OK (0) or a negative wg_status_t and never
  *     throws or exits; wg_last_error() describes the last failure on the
  *     calling thread.
- *   - Calls that take a stream only enqueue work: they do not synchronise,
- *     allocate or copy between host and device.  Calls on one handle must be
+ *   - The per-step calls only enqueue work on their stream: they do not
+ *     synchronise, allocate or copy between host and device -- except that a
+ *     fill with a batch larger than any before on the handle (and than 1,024)
+ *     first grows the handle's per-call lists, which synchronises the device
+ *     once.  wg_add_instances and wg_cache_resize say what they wait for.
+ *     Calls on one handle must be
  *     ordered on one stream (or otherwise serialised by the caller); the mask
  *     cache of a handle is shared state.
  */
