@@ -102,6 +102,7 @@ int ensure_batch(wg_handle_s *h, uint32_t B) {
     h->dc.row_ref = nullptr; h->dc.miss = nullptr; h->dc.class_miss = nullptr; h->max_batch = 0;
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.row_ref), nb * sizeof(uint32_t)));
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.miss), nb * sizeof(MissEntry)));
+    h->dc.miss_cap = nb;
     WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_miss), nb * sizeof(uint32_t)));
     h->max_batch = nb;
     return WG_OK;
@@ -179,7 +180,8 @@ int sync_table(wg_handle_s *h, hipStream_t s) {
                               hipMemcpyHostToDevice, s));
         for (uint32_t c = a; c < n_classes; c++) {
             ExitEntry *buf = nullptr;
-            WG_HIP(hipMalloc(reinterpret_cast<void **>(&buf), (size_t)V * sizeof(ExitEntry)));
+            // V slots for the list of the whole class table, V for the lists of its token ranges
+            WG_HIP(hipMalloc(reinterpret_cast<void **>(&buf), 2u * (size_t)V * sizeof(ExitEntry)));
             h->class_bufs.push_back(buf);
         }
         WG_HIP(hipMemcpyAsync(h->d_class_entries + a, h->class_bufs.data() + a, n * sizeof(ExitEntry *),
@@ -249,32 +251,44 @@ int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uin
     // Static indexes of the vocabulary (they depend on the token bytes only):
     //  - 8 bytes of padding so kernels may over-read a token's tail
     //  - len8 / chunks: fixed-stride view, 8 bytes per load, for the class scan
-    //  - first-byte buckets: the only tokens a literal state can admit
+    //  - first-byte buckets (per token range): the only tokens a literal state can admit
     //  - per-length rows: tokens with 1 <= length <= r, for Waits with a byte budget
     std::vector<uint8_t> bytes(total + 8, 0), len8(V, 0);
     if (total) std::memcpy(bytes.data(), host_bytes, total);
     std::vector<uint64_t> chunks((size_t)(n_chunks ? n_chunks : 1) * V, 0);
-    std::vector<uint32_t> lit_start(257, 0), len_rows((size_t)(lmax + 2) * rs, 0);
+    std::vector<uint32_t> lit_start(256 * kParts + 1, 0), len_rows((size_t)(lmax + 2) * rs, 0);
+    // the token ranges that can split the work of one mask row
+    uint32_t part_tok[kParts + 1];
+    const uint32_t n_groups = (V + kPartGroup - 1u) / kPartGroup;
+    for (uint32_t p = 0; p <= kParts; p++) {
+        const uint64_t t0 = ((uint64_t)p * n_groups / kParts) * kPartGroup;
+        part_tok[p] = (p == kParts || t0 > V) ? V : (uint32_t)t0;
+    }
+    auto part_of = [&](uint32_t t) {
+        uint32_t p = 0;
+        while (p + 1 < kParts && t >= part_tok[p + 1]) p++;
+        return p;
+    };
     for (uint32_t t = 0; t < V; t++) {
         uint32_t L = ((int64_t)t == eos_id) ? 0u : off[t + 1] - off[t];
         len8[t] = (uint8_t)L;
         for (uint32_t i = 0; i < L; i++)
             chunks[(size_t)(i / 8u) * V + t] |= (uint64_t)bytes[off[t] + i] << (8u * (i % 8u));
         if (L) {
-            lit_start[bytes[off[t]] + 1u]++;
+            lit_start[bytes[off[t]] * kParts + part_of(t) + 1u]++;
             for (uint32_t r = L; r <= lmax + 1u; r++) len_rows[(size_t)r * rs + (t >> 5)] |= 1u << (t & 31u);
         }
     }
-    for (int y = 0; y < 256; y++) lit_start[y + 1] += lit_start[y];
+    for (uint32_t y = 0; y < 256 * kParts; y++) lit_start[y + 1] += lit_start[y];
     // Within a bucket the entries are ordered by remaining length, so that the lanes of a
     // wavefront walk remainders of similar length.
-    std::vector<ExitEntry> lit_entries(lit_start[256] ? lit_start[256] : 1);
+    std::vector<ExitEntry> lit_entries(lit_start[256 * kParts] ? lit_start[256 * kParts] : 1);
     {
         std::vector<uint32_t> order;
         order.reserve(V);
         for (uint32_t t = 0; t < V; t++) if (len8[t]) order.push_back(t);
         std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
-            const uint32_t fa = bytes[off[a]], fb = bytes[off[b]];
+            const uint32_t fa = bytes[off[a]] * kParts + part_of(a), fb = bytes[off[b]] * kParts + part_of(b);
             return fa != fb ? fa < fb : len8[a] < len8[b];
         });
         for (size_t i = 0; i < order.size(); i++) {
@@ -298,7 +312,8 @@ int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uin
                     std::string("wg_vocab_create: ") + hipGetErrorString(e));
     }
     v->dv = DeviceVocab{v->d_bytes, v->d_offsets, v->d_len8, v->d_chunks, v->d_lit_entries,
-                        v->d_lit_start, v->d_len_rows, V, W, eos_id, lmax, n_chunks, rs};
+                        v->d_lit_start, v->d_len_rows, V, W, eos_id, lmax, n_chunks, rs, {}};
+    for (uint32_t p = 0; p <= kParts; p++) v->dv.part_tok[p] = part_tok[p];
     *out = v.release();
     return WG_OK;
 }
@@ -432,9 +447,13 @@ int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_t
 
     const uint32_t row_stride = vocab->dv.row_stride;
     const uint64_t row_bytes = (uint64_t)row_stride * 4ull;
-    if (row_bytes > 160ull * 1024ull)
-        return fail(WG_ERR_INVALID, "wg_compile: a mask row does not fit the 160 KB of LDS (vocabulary too large)");
-    WG_HIP(configure_kernels(row_stride * 4u));
+    {
+        const hipError_t e = configure_kernels(row_stride * 4u);
+        if (e == hipErrorInvalidValue)
+            return fail(WG_ERR_INVALID, "wg_compile: a mask row does not fit the LDS of a compute unit next to the "
+                                        "builder's queue (vocabulary too large)");
+        WG_HIP(e);
+    }
     h->dc.row_stride = row_stride;
     h->dc.epoch = 1;                                   // tags start at 0 = never built
 
@@ -443,7 +462,7 @@ int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_t
     size_t free_b = 0, total_b = 0;
     WG_HIP(hipMemGetInfo(&free_b, &total_b));
     const uint64_t n_classes = t.classes.size() / 256;
-    const uint64_t class_bytes = n_classes * (2ull * row_bytes + (uint64_t)vocab->dv.V * sizeof(ExitEntry));
+    const uint64_t class_bytes = n_classes * (2ull * row_bytes + 2ull * vocab->dv.V * sizeof(ExitEntry));
     if (class_bytes > (uint64_t)free_b / 4)
         return fail(WG_ERR_NOMEM, "wg_compile: the class indexes (" + std::to_string(class_bytes >> 20) +
                                       " MiB for " + std::to_string(n_classes) +
@@ -595,7 +614,7 @@ int wg_cache_stats(wg_handle_t h, wg_cache_stats_t *host_out) {
     host_out->rows_in_use = taken < h->dc.cap_rows ? taken : h->dc.cap_rows;
     const uint64_t row_bytes = (uint64_t)h->dc.row_stride * 4ull;
     host_out->arena_bytes = (uint64_t)h->dc.cap_rows * row_bytes +
-                            (uint64_t)h->class_bufs.size() * ((uint64_t)h->vocab->dv.V * sizeof(ExitEntry)) +
+                            (uint64_t)h->class_bufs.size() * (2ull * h->vocab->dv.V * sizeof(ExitEntry)) +
                             (uint64_t)h->cap_classes * 2ull * row_bytes;
     return WG_OK;
 }

@@ -8,6 +8,13 @@ namespace wg {
 
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;
 
+// The token ids are cut into kParts contiguous ranges (on 1024-token boundaries, so on 16-byte
+// boundaries of a mask row).  Every list of candidate tokens is kept per range, so that the
+// row of a state key whose candidates all need a deep walk can be built by several workgroups,
+// each owning the words of its ranges, without any merging.
+constexpr uint32_t kParts = 8;
+constexpr uint32_t kPartGroup = 1024;
+
 struct DeviceTable {
     const StateDesc *states;
     const uint8_t *classes;      // 256-byte class tables
@@ -31,14 +38,15 @@ struct DeviceVocab {
     const uint32_t *offsets;     // V + 1
     const uint8_t *len8;         // token length in bytes (0 for EOS and byte-less tokens)
     const uint64_t *chunks;      // chunks[k * V + t] = bytes 8k .. 8k+7 of token t, zero padded
-    const ExitEntry *lit_entries;   // tokens grouped by first byte (a literal state's candidates)
-    const uint32_t *lit_start;   // 257 bucket boundaries into lit_entries
+    const ExitEntry *lit_entries;   // tokens grouped by (first byte, range): a literal state's candidates
+    const uint32_t *lit_start;   // 256 * kParts + 1 bucket boundaries into lit_entries
     const uint32_t *len_rows;    // row r (0 .. lmax+1): tokens with 1 <= length <= r
     uint32_t V, W;
     int32_t eos_id;
     uint32_t lmax;
     uint32_t n_chunks;           // ceil(lmax / 8)
     uint32_t row_stride;         // words per mask row in device arenas (multiple of 4)
+    uint32_t part_tok[kParts + 1];  // first token of each range; part_tok[kParts] == V
 };
 
 // A successor state as key_build needs it for the first hop of a walk.
@@ -51,7 +59,7 @@ struct MissEntry {
     uint32_t key, sid, aux, kind;
     uint32_t r;                  // allow-bytes that may still be consumed, capped at lmax
     uint32_t cls;                // WAIT / COND: class table id
-    uint32_t ent_lo, ent_cnt;    // LIT: its first-byte bucket in the vocabulary's entry list
+    uint32_t lit, pad0;          // LIT: the byte (its first-byte buckets hold the candidates)
     uint32_t eos_next, next_a, next_b;
     uint32_t slot;               // arena row of the result, or kNoSlot: build into the bitmask row of `req`
     uint32_t req;                // the request that claimed the key
@@ -61,7 +69,9 @@ struct MissEntry {
 static_assert(sizeof(MissEntry) == 112, "miss entry layout");
 
 struct Counters {
-    uint32_t n_miss;             // state keys to build in the call in flight
+    uint32_t n_deep;             // keys of the call in flight whose candidates all need a deep walk
+    uint32_t n_plain;            // ... and the other keys (the two share the miss list, from its two ends)
+    uint32_t n_claims;           // state keys claimed in the call in flight
     uint32_t n_class_miss;       // class tables to scan in the call in flight
     unsigned long long slot_ctr; // generation << 32 | arena rows in use in that generation (<= cap_rows)
     unsigned long long launch;   // number of the fill call in flight (its gather counts it up)
@@ -95,11 +105,15 @@ struct DeviceCache {
     // per class table (the context-free part of every mask of a state using that table)
     uint32_t *class_built;       // generation in which the class index was built
     uint32_t *class_rows;        // 2 rows per class: [stay] all bytes stay, [end] exits on its last byte
-    ExitEntry *const *class_entries;   // per class: V entries, filled from both ends
-    uint32_t *class_count;       // entries in use per class (front, back), 128 bytes apart
+    ExitEntry *const *class_entries;   // per class 2 V slots: [0, V) the list of the class table, range p of
+                                 // the second V owns [V + part_tok[p], V + part_tok[p+1]); each filled
+                                 // from both ends
+    uint32_t *class_count;       // per class 2 + 2 * kParts counters (front, back of the class list, then of
+                                 // each range), 128 bytes apart
     // per call
     uint32_t *row_ref;           // [B] arena row of the request's mask, kRefByKey | key, or kNoKey
-    MissEntry *miss;             // [B]
+    MissEntry *miss;             // [miss_cap]: deep keys from the front, plain keys from the back
+    uint32_t miss_cap;           // the largest batch so far
     uint32_t *class_miss;        // [B]
     uint32_t row_stride;         // words, multiple of 4
     uint32_t n_keys;

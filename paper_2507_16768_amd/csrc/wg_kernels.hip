@@ -19,6 +19,8 @@
 namespace wg {
 
 constexpr uint32_t kScanGroup = 1024;     // tokens per class_scan workgroup
+static_assert(kScanGroup == kPartGroup, "a class_scan workgroup's tokens lie in one token range");
+static_assert(2u + 2u * kParts <= 32u, "the counters of a class fit its 128 bytes");
 constexpr uint32_t kCountStride = 32;     // class_count entries are 128 bytes apart
 constexpr uint32_t kXcds = 8;             // accelerator complex dies, each with a private L2
 constexpr uint32_t kShortRem = 4;         // exit entries with at most this many bytes left are "short"
@@ -134,8 +136,8 @@ __device__ __forceinline__ bool walk_chunks(const DeviceTable &T, uint32_t &sid,
 // lookup: state -> cache key.  A missing key is claimed by exactly one request (CAS on the
 // key's tag), gets a row of the arena (or, when the arena is full, is built straight into
 // the claimer's bitmask row and not kept) and is queued for key_build: the i-th claim of a call
-// takes the i-th free row, so the claims' position in the miss list is their row allocation and
-// the count of rows in use is brought up to date once per call, by gather; if the key's state is a
+// takes the i-th free row, so the order of the claims is their row allocation and the count
+// of rows in use is brought up to date once per call, by the last kernel of the fill; if the key's state is a
 // checkpoint whose class table has no index yet in this generation, the table is claimed and
 // queued for class_scan.
 
@@ -163,7 +165,8 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceVoc
     const unsigned long long launch = env.launch;
     const uint32_t rows0 = env.rows0;
     uint32_t ref = kNoKey;
-    StateDesc d{};
+    StateDesc d{}, dn[2] = {};
+    uint32_t class_gen = 0;
     if (live) {
         if (sid < T.n_states) {
             d = T.states[sid];
@@ -174,6 +177,13 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceVoc
             }
             key = d.key_base + variant;
             const unsigned long long t = __hip_atomic_load(&Cc.tags[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // Requested right behind the key's tag, although only a missing key needs them: the
+            // two successors' descriptors and the generation of the class index.  Plain loads
+            // from clamped indexes, so that nothing waits for them before the tag has decided.
+            dn[0] = T.states[d.next_a < T.n_states ? d.next_a : 0u];
+            dn[1] = T.states[d.next_b < T.n_states ? d.next_b : 0u];
+            class_gen = __hip_atomic_load(&Cc.class_built[(kind == WG_KIND_WAIT || kind == WG_KIND_COND) ? d.cls : 0u],
+                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             // anything but a row of this generation or a claim made in this very call is stale
             hit = (uint32_t)(t >> 32) == epoch;
             const bool this_call = t >= kTagClaim && ((t >> 16) & kTagLaunchMask) == launch;
@@ -183,14 +193,38 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceVoc
         }
         Cc.row_ref[b] = ref;
     }
-    // the claimers of a wavefront take their places in the miss list together
+    // The claimers of a wavefront take their arena rows and their places in the miss list
+    // together.  A key whose candidate tokens all need a deep walk (its state hands over to
+    // another checkpoint) goes to the front of the list: key_build cuts it into one work item per
+    // token range and starts those first; every other key is one work item, from the back.
     const unsigned long long cm = __ballot(claimed);
     if (cm) {
-        uint32_t first = 0;
-        if (lane == (uint32_t)__builtin_ctzll(cm)) first = atomicAdd(&Cc.ctr->n_miss, (uint32_t)__popcll(cm));
-        first = __shfl(first, __builtin_ctzll(cm));
+        HopState hop[2];
+        bool deep = false;
         if (claimed) {
-            const uint32_t idx = first + (uint32_t)__popcll(cm & ((1ull << lane) - 1ull));
+#pragma unroll
+            for (int w = 0; w < 2; w++) {
+                const uint32_t t = w ? d.next_b : d.next_a;
+                const StateDesc &td = dn[w];
+                hop[w] = HopState{0xFFu, 0u, WG_SID_ERROR, WG_SID_ERROR, WG_UNBOUNDED, 0u};
+                if (t < T.n_states)
+                    hop[w] = HopState{td.kind_byte & 0xFFu, (td.kind_byte >> 8) & 0xFFu,
+                                      td.next_a, td.next_b, td.max, td.cls};
+            }
+            const bool ckpt0 = hop[0].kind == WG_KIND_WAIT || hop[0].kind == WG_KIND_COND;
+            const bool ckpt1 = hop[1].kind == WG_KIND_WAIT || hop[1].kind == WG_KIND_COND;
+            deep = ((kind == WG_KIND_LIT || kind == WG_KIND_WAIT) && ckpt0) || (kind == WG_KIND_COND && (ckpt0 || ckpt1));
+        }
+        const unsigned long long dm = __ballot(claimed && deep), pm = cm & ~dm;
+        // three counters, three lanes: the atomics are in flight together
+        uint32_t got = 0;
+        if (lane == 0) got = atomicAdd(&Cc.ctr->n_claims, (uint32_t)__popcll(cm));
+        else if (lane == 1 && dm) got = atomicAdd(&Cc.ctr->n_deep, (uint32_t)__popcll(dm));
+        else if (lane == 2 && pm) got = atomicAdd(&Cc.ctr->n_plain, (uint32_t)__popcll(pm));
+        const uint32_t first_key = __shfl(got, 0), first_deep = __shfl(got, 1), first_plain = __shfl(got, 2);
+        if (claimed) {
+            const unsigned long long below = (1ull << lane) - 1ull;
+            const uint32_t idx = first_key + (uint32_t)__popcll(cm & below);
             const uint32_t slot = Cc.cap_rows - rows0 > idx ? rows0 + idx : kNoSlot;
             // this request builds the key: resolve what key_build needs into the miss entry
             MissEntry me{};
@@ -198,28 +232,18 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceVoc
             me.r = T.lmax - variant; me.cls = d.cls; me.eos_next = d.eos_next;
             me.next_a = d.next_a; me.next_b = d.next_b;
             me.slot = slot; me.req = b;
-            if (kind == WG_KIND_LIT) {
-                const uint32_t y = (d.kind_byte >> 8) & 0xFFu;
-                me.ent_lo = Vc.lit_start[y];
-                me.ent_cnt = Vc.lit_start[y + 1u] - me.ent_lo;
-            }
-#pragma unroll
-            for (int w = 0; w < 2; w++) {
-                const uint32_t t = w ? d.next_b : d.next_a;
-                me.hop[w] = HopState{0xFFu, 0u, WG_SID_ERROR, WG_SID_ERROR, WG_UNBOUNDED, 0u};
-                if (t < T.n_states) {
-                    const StateDesc &td = T.states[t];
-                    me.hop[w] = HopState{td.kind_byte & 0xFFu, (td.kind_byte >> 8) & 0xFFu,
-                                         td.next_a, td.next_b, td.max, td.cls};
-                }
-            }
-            Cc.miss[idx] = me;
+            me.hop[0] = hop[0]; me.hop[1] = hop[1];
+            me.lit = (d.kind_byte >> 8) & 0xFFu;
+            Cc.miss[deep ? first_deep + (uint32_t)__popcll(dm & below)
+                         : Cc.miss_cap - 1u - (first_plain + (uint32_t)__popcll(pm & below))] = me;
             if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
                 const uint32_t c = d.cls;
-                const uint32_t oc = __hip_atomic_load(&Cc.class_built[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const uint32_t oc = class_gen;
                 if (oc != epoch && atomicCAS(&Cc.class_built[c], oc, epoch) == oc) {
-                    Cc.class_count[c * kCountStride] = 0;          // short entries, from the front
-                    Cc.class_count[c * kCountStride + 1u] = 0;     // long entries, from the back
+                    // the class list and the list of each token range: short entries fill from the
+                    // front, long ones from the back
+#pragma unroll
+                    for (uint32_t i = 0; i < 2u + 2u * kParts; i++) Cc.class_count[c * kCountStride + i] = 0;
                     Cc.class_miss[atomicAdd(&Cc.ctr->n_class_miss, 1u)] = c;
                 }
             }
@@ -283,7 +307,9 @@ __global__ void __launch_bounds__(256)
 class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lut[256];
-    __shared__ uint32_t seg[2][17];                  // short / long entries per (wave, slice), then offsets
+    __shared__ uint32_t seg[2][16];                  // short / long entries per (wave, slice)
+    __shared__ uint32_t seg_pre[2][16];              // ... summed up: where each (wave, slice) starts within the workgroup
+    __shared__ uint32_t seg_base[2][2];              // where this workgroup's entries start in the two lists
     const uint32_t n = Cc.ctr->n_class_miss;
     const uint32_t groups = (Vc.V + kScanGroup - 1u) / kScanGroup;
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
@@ -299,6 +325,9 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
     for (uint64_t item = local; item < total; item += local_wgs) {
         const uint32_t c = Cc.class_miss[(uint32_t)(item % n)];
         const uint32_t g = (uint32_t)(item / n) * nx + xcd;
+        uint32_t part = 0;
+#pragma unroll
+        for (uint32_t q = 1; q < kParts; q++) part += g * kScanGroup >= Vc.part_tok[q];
         __syncthreads();
         if (threadIdx.x < 64u)
             reinterpret_cast<uint32_t *>(lut)[threadIdx.x] =
@@ -353,18 +382,22 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
             if (lane == 0) { seg[0][wave * 4u + s] = (uint32_t)__popcll(bx[s]); seg[1][wave * 4u + s] = (uint32_t)__popcll(by[s]); }
         }
         __syncthreads();
-        // Entries with a short remainder fill the class's list from the front, the others from
-        // the back, so that a wavefront of key_build walks remainders of similar length.
-        if (threadIdx.x < 2u) {
-            const uint32_t side = threadIdx.x;
+        // Entries with a short remainder fill a list from the front, the others from the back, so
+        // that a wavefront of key_build walks remainders of similar length.  Every entry goes to
+        // two lists: the one of the whole class table (first V slots of the class's buffer), read
+        // by keys that are built by one workgroup, and the one of its token range (second V
+        // slots, range p owning [V + part_tok[p], V + part_tok[p+1])), read by the work items of
+        // keys that are cut by range.
+        if (threadIdx.x < 4u) {
+            const uint32_t side = threadIdx.x & 1u, which = threadIdx.x >> 1;     // which: 0 class, 1 range
             uint32_t sum = 0;
-            for (int i = 0; i < 16; i++) { uint32_t x = seg[side][i]; seg[side][i] = sum; sum += x; }
-            const uint32_t base = sum ? atomicAdd(&Cc.class_count[c * kCountStride + side], sum) : 0u;
-            for (int i = 0; i < 16; i++) seg[side][i] += base;
-            seg[side][16] = sum;
+            for (int i = 0; i < 16; i++) { if (which == 0u) seg_pre[side][i] = sum; sum += seg[side][i]; }
+            const uint32_t ctr = which ? 2u + 2u * part + side : side;
+            seg_base[which][side] = sum ? atomicAdd(&Cc.class_count[c * kCountStride + ctr], sum) : 0u;
         }
         __syncthreads();
         ExitEntry *out = Cc.class_entries[c];
+        const uint32_t out_lo = V + Vc.part_tok[part], out_hi = V + Vc.part_tok[part + 1u];
 #pragma unroll
         for (int s = 0; s < 4; s++) {
             const bool sh = (bx[s] >> lane) & 1ull, lg = (by[s] >> lane) & 1ull;
@@ -380,25 +413,30 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
                 ExitEntry e;
                 e.tok = tk[s]; e.off = (uint8_t)nx; e.cls = (uint8_t)res[s];
                 e.first = (uint8_t)first; e.rem = (uint8_t)(L[s] - nx);
-                const uint32_t pos = seg[sh ? 0 : 1][wave * 4u + s] + rank;
-                out[sh ? pos : V - 1u - pos] = e;
+                const uint32_t in_wg = seg_pre[sh ? 0 : 1][wave * 4u + s] + rank;
+                const uint32_t pos_c = seg_base[0][sh ? 0 : 1] + in_wg, pos_r = seg_base[1][sh ? 0 : 1] + in_wg;
+                out[sh ? pos_c : V - 1u - pos_c] = e;
+                out[sh ? out_lo + pos_r : out_hi - 1u - pos_r] = e;
             }
         }
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&Cc.ctr->class_scans, (unsigned long long)n);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && n) atomicAdd(&Cc.ctr->class_scans, (unsigned long long)n);
 }
 
 // ---------------------------------------------------------------------------------------------
-// key_build: one workgroup per missing state key assembles the key's mask row in LDS:
+// key_build: a workgroup assembles the mask row of a missing state key in LDS -- or, for a key
+// whose candidates all need a deep walk, its words for one of the kParts token ranges, so that
+// such a key is shared among kParts workgroups instead of holding up the whole launch:
 //   (a) the context-free part from the class index (budget-limited through the per-length
 //       rows of the vocabulary), zeros for a literal / END / FINAL state;
 //   (b) the tokens that leave the state early (exit list of the class table, or the
-//       first-byte bucket of a literal state): the rest of each such token is walked from
-//       the successor state, and an accepted token sets its bit with an LDS atomic.  The two
-//       possible successors are workgroup-uniform, so their descriptors and class tables are
-//       staged in LDS and the first hop of every walk runs out of LDS and registers; only a
-//       token that leaves the successor as well continues through the table in HBM;
-//   (c) the EOS bit, then the row goes to the cache arena.
+//       first-byte buckets of a literal state): first all of them are filtered, then the rest
+//       of each survivor is walked from the successor state, and an accepted token sets its bit
+//       with an LDS atomic.  The two possible successors are workgroup-uniform, so their
+//       descriptors and class tables are staged in LDS and the first hop of every walk runs out
+//       of LDS and registers; only a token that leaves the successor as well continues through
+//       the table in HBM;
+//   (c) the EOS bit, then the words go to the cache arena.
 __device__ __forceinline__ uint32_t token_byte(uint64_t c0, uint64_t c1, uint64_t c2, uint32_t i)
 {
     const uint64_t cw = i < 8u ? c0 : i < 16u ? c1 : c2;
@@ -432,30 +470,75 @@ __device__ __forceinline__ bool walk_first_hop(const DeviceTable &T, const HopSt
     return walk_chunks(T, sid, aux, c0, c1, c2, i, L);
 }
 
-__global__ void __launch_bounds__(1024)
+constexpr uint32_t kKbThreads = 512;       // two workgroups per compute unit
+constexpr uint32_t kKbWaves = kKbThreads / 64u;
+constexpr uint32_t kKbPer = 12;            // candidates a thread filters per pass
+constexpr uint32_t kKbQueue = kKbThreads * kKbPer;   // candidates waiting for their walk: a whole pass fits (48 KB of LDS)
+typedef __attribute__((address_space(1))) uint2 global_u2;   // a load known to go to device memory
+
+// Walks what is left of a candidate token from the state its exit leads to.
+__device__ __forceinline__ bool walk_candidate(const DeviceTable &T, const DeviceVocab &Vc, const MissEntry &me,
+                                               const uint8_t (*hop_lut)[256], const ExitEntry &x, bool regs_ok)
+{
+    const int w = x.cls == CLS_EXIT_B;
+    if (regs_ok) {
+        const uint32_t L = (uint32_t)x.off + x.rem;
+        const uint64_t c0 = Vc.chunks[x.tok];
+        const uint64_t c1 = L > 8u ? Vc.chunks[(size_t)Vc.V + x.tok] : 0ull;
+        const uint64_t c2 = L > 16u ? Vc.chunks[2ull * Vc.V + x.tok] : 0ull;
+        return walk_first_hop(T, me.hop[w], hop_lut[w], c0, c1, c2, x.off, L);
+    }
+    uint32_t sid = w ? me.next_b : me.next_a, aux = 0;
+    return walk_bytes(T, sid, aux, Vc.bytes + Vc.offsets[x.tok] + x.off, x.rem);
+}
+
+__global__ void __launch_bounds__(kKbThreads) __attribute__((amdgpu_waves_per_eu(4, 4)))
 key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__restrict__ bitmask)
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t row[];
     __shared__ __attribute__((aligned(16))) uint8_t hop_lut[2][256];
-    const uint32_t n_miss = Cc.ctr->n_miss;
-    const uint32_t rs = Cc.row_stride, rs4 = rs / 4u, tid = threadIdx.x, V = Vc.V;
+    __shared__ uint2 queue[kKbQueue];
+    __shared__ uint32_t queued;
+    // The first quarter of the grid serves the deep items (front of the miss list), the rest the
+    // plain ones (back), so that where a workgroup's first item lies does not depend on the counts.
+    const uint32_t deep_wgs = gridDim.x / 4u ? gridDim.x / 4u : 1u;
+    const bool serves_deep = blockIdx.x < deep_wgs || gridDim.x == 1u;
+    const bool serves_plain = blockIdx.x >= deep_wgs || gridDim.x == 1u;
+    const uint32_t n_deep = Cc.ctr->n_deep, n_plain = Cc.ctr->n_plain, n_claims = Cc.ctr->n_claims;
+    const uint32_t rs = Cc.row_stride, tid = threadIdx.x, lane = tid & 63u;
     const bool regs_ok = Vc.lmax <= 24u;             // a whole token fits three 8-byte chunks
-    for (uint32_t m = blockIdx.x; m < n_miss; m += gridDim.x) {
-        const MissEntry me = Cc.miss[m];
+    for (uint32_t list = 0; list < 2u; list++) {
+    if (list == 0u ? !serves_deep : !serves_plain) continue;
+    const uint32_t n_list = list == 0u ? n_deep * kParts : n_plain;    // a deep key is kParts work items
+    const uint32_t i_first = list == 0u || gridDim.x == 1u ? blockIdx.x : blockIdx.x - deep_wgs;
+    const uint32_t i_step = gridDim.x == 1u ? 1u : list == 0u ? deep_wgs : gridDim.x - deep_wgs;
+    for (uint32_t item = i_first; item < n_list; item += i_step) {
+        const MissEntry me = Cc.miss[list == 0u ? item / kParts : Cc.miss_cap - 1u - item];
         const uint32_t kind = me.kind, r = me.r;
+        const uint32_t p0 = list == 0u ? item % kParts : 0u, span = list == 0u ? 1u : kParts;
+        // this item's words of the row, in 16-byte units
+        const uint32_t q_lo = Vc.part_tok[p0] >> 7;
+        const uint32_t q_hi = p0 + span == kParts ? rs / 4u : Vc.part_tok[p0 + span] >> 7;
+        // Its candidate tokens, ents[i < n_front ? at_front + i : at_back + i - n_front]: the
+        // first-byte buckets of a literal state (contiguous over these ranges), or the two-ended
+        // list of a checkpoint's class table: the whole one, or the one of range p0.
         const ExitEntry *ents = nullptr;
-        uint32_t cnt = 0, n_front = 0xFFFFFFFFu, back = 0;
+        uint32_t cnt = 0, n_front = 0, at_front = 0, at_back = 0;
         const uint4 *stay = nullptr, *end = nullptr;
         if (kind == WG_KIND_LIT) {
-            ents = Vc.lit_entries + me.ent_lo;
-            cnt = me.ent_cnt;
+            ents = Vc.lit_entries;
+            at_front = Vc.lit_start[me.lit * kParts + p0];
+            cnt = n_front = Vc.lit_start[me.lit * kParts + p0 + span] - at_front;
         } else if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
             ents = Cc.class_entries[me.cls];
-            n_front = Cc.class_count[me.cls * kCountStride];
-            cnt = n_front + Cc.class_count[me.cls * kCountStride + 1u];
-            back = V - cnt;                           // index i >= n_front lives at i + back
+            const uint32_t *cc = Cc.class_count + me.cls * kCountStride + (span == kParts ? 0u : 2u + 2u * p0);
+            n_front = cc[0];
+            const uint32_t n_back = cc[1];
+            cnt = n_front + n_back;
+            at_front = span == kParts ? 0u : Vc.V + Vc.part_tok[p0];
+            at_back = (span == kParts ? Vc.V : Vc.V + Vc.part_tok[p0 + 1u]) - n_back;
             stay = reinterpret_cast<const uint4 *>(Cc.class_rows + (size_t)(2u * me.cls) * rs);
-            end = stay + rs4;
+            end = stay + rs / 4u;
         }
         // the two possible successors: class tables staged in LDS for the first hop
 #pragma unroll
@@ -463,12 +546,13 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
             if ((me.hop[w].kind == WG_KIND_WAIT || me.hop[w].kind == WG_KIND_COND) && tid < 64u)
                 reinterpret_cast<uint32_t *>(hop_lut[w])[tid] =
                     reinterpret_cast<const uint32_t *>(T.classes + (size_t)me.hop[w].cls * 256u)[tid];
+        if (tid == 0) queued = 0;
         // (a)
         uint4 *row4 = reinterpret_cast<uint4 *>(row);
         if (!stay) {
-            for (uint32_t q = tid; q < rs4; q += blockDim.x) row4[q] = uint4{0u, 0u, 0u, 0u};
+            for (uint32_t q = q_lo + tid; q < q_hi; q += kKbThreads) row4[q] = uint4{0u, 0u, 0u, 0u};
         } else if (r >= Vc.lmax) {
-            for (uint32_t q = tid; q < rs4; q += blockDim.x) {
+            for (uint32_t q = q_lo + tid; q < q_hi; q += kKbThreads) {
                 const uint4 a = stay[q], b = end[q];
                 row4[q] = uint4{a.x | b.x, a.y | b.y, a.z | b.z, a.w | b.w};
             }
@@ -476,85 +560,101 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
             // r allow-bytes may still be consumed: all-stay tokens need length <= r, tokens
             // that exit on their last byte have length - 1 stay bytes
             const uint4 *l0 = reinterpret_cast<const uint4 *>(Vc.len_rows + (size_t)r * rs);
-            const uint4 *l1 = l0 + rs4;
-            for (uint32_t q = tid; q < rs4; q += blockDim.x) {
+            const uint4 *l1 = l0 + rs / 4u;
+            for (uint32_t q = q_lo + tid; q < q_hi; q += kKbThreads) {
                 const uint4 a = stay[q], b = end[q], x = l0[q], y = l1[q];
                 row4[q] = uint4{(a.x & x.x) | (b.x & y.x), (a.y & x.y) | (b.y & y.y),
                                 (a.z & x.z) | (b.z & y.z), (a.w & x.w) | (b.w & y.w)};
             }
         }
         __syncthreads();
-        // (b) four entries per thread and pass, so their loads are in flight together
-        for (uint32_t i0 = tid; i0 < cnt; i0 += 4u * blockDim.x) {
-            ExitEntry x[4];
-            bool walk[4];
-            uint64_t c0[4], c1[4], c2[4];
+        // (b) The candidates, kKbThreads * kKbPer per pass.  (b1) filter: every candidate is
+        // looked at once, kKbPer per thread, all loaded before any is used (plain 8-byte loads
+        // from clamped indexes: a load inside a branch would be waited for on the spot).  One
+        // that ends with its exit byte is accepted at once, one whose next byte cannot start the
+        // literal that follows is dropped, the others wait in LDS for (b2) their walk -- so that
+        // the walks, each a chain of dependent loads, run densely packed instead of a few lanes of
+        // every wavefront holding the others up.
+        constexpr uint32_t kAnyByte = 0x100u;        // no literal follows this exit
+        const uint32_t next_lit[2] = {me.hop[0].kind == WG_KIND_LIT ? me.hop[0].lit : kAnyByte,
+                                      me.hop[1].kind == WG_KIND_LIT ? me.hop[1].lit : kAnyByte};
+        const global_u2 *ents2 = (const global_u2 *)ents;
+        for (uint32_t i0 = 0; i0 < cnt; i0 += kKbThreads * kKbPer) {
+            uint2 x[kKbPer];
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
-                const uint32_t i = i0 + u * blockDim.x;
-                x[u] = i < cnt ? ents[i < n_front ? i : i + back] : ExitEntry{0u, 255u, 0u, 0u, 0u};   // off 255 fails the budget test
+            for (uint32_t j = 0; j < kKbPer; j++) {
+                uint32_t i = i0 + j * kKbThreads + tid;
+                i = i < cnt ? i : cnt - 1u;
+                const global_u2 *src = ents2 + (i < n_front ? at_front + i : at_back + (i - n_front));
+                x[j] = uint2{src->x, src->y};
             }
+            uint32_t slot[kKbPer], in_wave = 0;               // place among the wavefront's candidates to walk
+            uint32_t need = 0;                                   // bit j: x[j] has to be walked
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
-                const bool in_budget = (uint32_t)x[u].off - 1u <= r;
-                const HopState &h = me.hop[x[u].cls == CLS_EXIT_B];
-                walk[u] = in_budget && x[u].rem != 0 && !(h.kind == WG_KIND_LIT && x[u].first != h.lit);
-                if (in_budget && x[u].rem == 0) atomicOr(&row[x[u].tok >> 5], 1u << (x[u].tok & 31u));
-                c0[u] = c1[u] = c2[u] = 0;
-                if (walk[u] && regs_ok) {
-                    const uint32_t L = (uint32_t)x[u].off + x[u].rem;
-                    c0[u] = Vc.chunks[x[u].tok];
-                    if (L > 8u) c1[u] = Vc.chunks[(size_t)V + x[u].tok];
-                    if (L > 16u) c2[u] = Vc.chunks[2ull * V + x[u].tok];
-                }
+            for (uint32_t j = 0; j < kKbPer; j++) {
+                const uint32_t off = x[j].y & 0xFFu, cls = (x[j].y >> 8) & 0xFFu, first = (x[j].y >> 16) & 0xFFu, rem = x[j].y >> 24;
+                const bool live = i0 + j * kKbThreads + tid < cnt && off - 1u <= r;
+                const uint32_t lit = cls == CLS_EXIT_B ? next_lit[1] : next_lit[0];
+                const bool walk = live && rem != 0 && (lit == kAnyByte || first == lit);
+                if (live && rem == 0) atomicOr(&row[x[j].x >> 5], 1u << (x[j].x & 31u));
+                const unsigned long long wm = __ballot(walk);
+                slot[j] = in_wave + (uint32_t)__popcll(wm & ((1ull << lane) - 1ull));
+                in_wave += (uint32_t)__popcll(wm);
+                need |= (uint32_t)walk << j;
             }
+            if (in_wave) {                                       // one LDS atomic per wavefront and pass
+                uint32_t base = 0;
+                if (lane == 0) base = atomicAdd(&queued, in_wave);
+                base = __shfl(base, 0);
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
-                if (!walk[u]) continue;
-                const int w = x[u].cls == CLS_EXIT_B;
-                bool ok;
-                if (regs_ok) {
-                    ok = walk_first_hop(T, me.hop[w], hop_lut[w], c0[u], c1[u], c2[u],
-                                        x[u].off, (uint32_t)x[u].off + x[u].rem);
-                } else {
-                    uint32_t sid = w ? me.next_b : me.next_a, aux = 0;
-                    ok = walk_bytes(T, sid, aux, Vc.bytes + Vc.offsets[x[u].tok] + x[u].off, x[u].rem);
-                }
-                if (ok) atomicOr(&row[x[u].tok >> 5], 1u << (x[u].tok & 31u));
+                for (uint32_t j = 0; j < kKbPer; j++)
+                    if ((need >> j) & 1u) queue[base + slot[j]] = x[j];
             }
+            __syncthreads();
+            // (b2) walk the queued candidates, one per thread and round
+            const uint32_t n_queued = queued;
+            for (uint32_t i = tid; i < n_queued; i += kKbThreads) {
+                const uint2 q = queue[i];
+                ExitEntry e;
+                e.tok = q.x; e.off = (uint8_t)q.y; e.cls = (uint8_t)(q.y >> 8); e.first = (uint8_t)(q.y >> 16); e.rem = (uint8_t)(q.y >> 24);
+                if (walk_candidate(T, Vc, me, hop_lut, e, regs_ok)) atomicOr(&row[e.tok >> 5], 1u << (e.tok & 31u));
+            }
+            __syncthreads();
+            if (tid == 0) queued = 0;
         }
         __syncthreads();
         if (tid == 0) atomicAdd(&Cc.ctr->entries_walked, (unsigned long long)cnt);
-        if (tid == 0 && Vc.eos_id >= 0 && me.eos_next != WG_SID_ERROR)
-            row[(uint32_t)Vc.eos_id >> 5] |= 1u << ((uint32_t)Vc.eos_id & 31u);
+        if (tid == 0 && Vc.eos_id >= 0 && me.eos_next != WG_SID_ERROR) {
+            const uint32_t ew = (uint32_t)Vc.eos_id >> 5;
+            if (ew >= 4u * q_lo && ew < 4u * q_hi) row[ew] |= 1u << ((uint32_t)Vc.eos_id & 31u);
+        }
         __syncthreads();
         // (c) to its arena row, or, if the arena had no row left, to the claimer's bitmask row
         if (me.slot != kNoSlot) {
             uint4 *dst = reinterpret_cast<uint4 *>(Cc.arena + (size_t)me.slot * rs);
-            for (uint32_t q = tid; q < rs4; q += blockDim.x) dst[q] = row4[q];
-            if (tid == 0) Cc.tags[me.key] = ((unsigned long long)Cc.epoch << 32) | me.slot;
+            for (uint32_t q = q_lo + tid; q < q_hi; q += kKbThreads) dst[q] = row4[q];
+            if (tid == 0 && p0 == 0) Cc.tags[me.key] = ((unsigned long long)Cc.epoch << 32) | me.slot;
         } else {
             uint32_t *dst = bitmask + (size_t)me.req * Vc.W;
-            for (uint32_t w = tid; w < Vc.W; w += blockDim.x) dst[w] = row[w];
+            const uint32_t w_hi = 4u * q_hi < Vc.W ? 4u * q_hi : Vc.W;
+            for (uint32_t w = 4u * q_lo + tid; w < w_hi; w += kKbThreads) dst[w] = row[w];
         }
         __syncthreads();
     }
-    if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&Cc.ctr->builds, (unsigned long long)n_miss);
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0 && n_claims) atomicAdd(&Cc.ctr->builds, (unsigned long long)n_claims);
 }
 
-// gather: bitmask[b] <- the row of request b's key (zeros without a key): from the arena, or
-// from the bitmask row of the request that built it when the row could not be kept.  Rows are
-// copied 16 bytes per thread when the caller's row stride allows it.
 // The miss lists have been consumed by the kernels that ran before the last kernel of a fill:
 // one thread of it counts their rows as used and empties them for the next call.
 __device__ __forceinline__ void close_fill(const DeviceCache &Cc)
 {
     const unsigned long long sc = Cc.ctr->slot_ctr;
     const uint32_t used = (uint32_t)(sc >> 32) == Cc.epoch ? (uint32_t)sc : 0u;
-    const uint32_t room = Cc.cap_rows - used, n = Cc.ctr->n_miss;
+    const uint32_t room = Cc.cap_rows - used, n = Cc.ctr->n_claims;
     if (n > room) Cc.ctr->uncached_builds += n - room;
     Cc.ctr->slot_ctr = ((unsigned long long)Cc.epoch << 32) | (used + (n < room ? n : room));
-    Cc.ctr->n_miss = 0; Cc.ctr->n_class_miss = 0;
+    Cc.ctr->n_deep = 0; Cc.ctr->n_plain = 0; Cc.ctr->n_claims = 0; Cc.ctr->n_class_miss = 0;
     Cc.ctr->launch++;
 }
 
@@ -919,9 +1019,15 @@ select_kernel(const uint32_t *__restrict__ bitmask, uint32_t W, const uint64_t *
 
 static inline uint32_t cdiv(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
 
+// key_build keeps a whole mask row (dynamic LDS) next to its candidate queue and tables (static
+// LDS); together they may pass the 64 KB a kernel gets without asking.  Returns
+// hipErrorInvalidValue when a row does not fit the 160 KB of a compute unit at all.
 hipError_t configure_kernels(uint32_t row_bytes)
 {
-    if (row_bytes <= 64u * 1024u) return hipSuccess;
+    hipFuncAttributes attr;
+    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(key_build_kernel));
+    if (e != hipSuccess) return e;
+    if (attr.sharedSizeBytes + (size_t)row_bytes > 160u * 1024u) return hipErrorInvalidValue;
     return hipFuncSetAttribute(reinterpret_cast<const void *>(key_build_kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)row_bytes);
 }
@@ -957,8 +1063,10 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
     uint32_t cap = n_cu * 8u;
     launch(class_scan_kernel, dim3(scan_items < cap ? (uint32_t)scan_items : cap), dim3(256), 0, s,
            ev ? ev + 2 : nullptr, T, Vc, Cc);
-    uint32_t kb = n_cu * 2u;
-    launch(key_build_kernel, dim3(B < kb ? B : kb), dim3(1024), Cc.row_stride * 4u, s,
+    // up to kParts work items per key; two 512-thread workgroups fit a compute unit
+    const uint32_t kb = n_cu * 2u;
+    const uint64_t kb_items = (uint64_t)B * kParts;
+    launch(key_build_kernel, dim3(kb_items < kb ? (uint32_t)kb_items : kb), dim3(kKbThreads), Cc.row_stride * 4u, s,
            ev ? ev + 4 : nullptr, T, Vc, Cc, bitmask);
     hipEvent_t *ge = ev ? ev + 6 : nullptr;
     if (logits && apply_vec_ok(logits, dtype, Vc.V, logits_stride)) {
