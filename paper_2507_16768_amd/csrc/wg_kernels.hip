@@ -512,8 +512,15 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
     const uint32_t n_list = list == 0u ? n_deep * kParts : n_plain;    // a deep key is kParts work items
     const uint32_t i_first = list == 0u || gridDim.x == 1u ? blockIdx.x : blockIdx.x - deep_wgs;
     const uint32_t i_step = gridDim.x == 1u ? 1u : list == 0u ? deep_wgs : gridDim.x - deep_wgs;
+    // Where a workgroup's first entry lies depends on its place in the grid only, so it is
+    // requested before the counts are known (and ignored if there is no such item).
+    auto entry_of = [&](uint32_t item) {
+        const uint32_t at = list == 0u ? item / kParts : Cc.miss_cap - 1u - item;
+        return at < Cc.miss_cap ? at : 0u;
+    };
+    MissEntry me = Cc.miss[entry_of(i_first)];
     for (uint32_t item = i_first; item < n_list; item += i_step) {
-        const MissEntry me = Cc.miss[list == 0u ? item / kParts : Cc.miss_cap - 1u - item];
+        if (item != i_first) me = Cc.miss[entry_of(item)];
         const uint32_t kind = me.kind, r = me.r;
         const uint32_t p0 = list == 0u ? item % kParts : 0u, span = list == 0u ? 1u : kParts;
         // this item's words of the row, in 16-byte units
@@ -592,6 +599,7 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
             uint32_t need = 0;                                   // bit j: x[j] has to be walked
 #pragma unroll
             for (uint32_t j = 0; j < kKbPer; j++) {
+                if (i0 + j * kKbThreads >= cnt) break;        // no candidate left for any thread
                 const uint32_t off = x[j].y & 0xFFu, cls = (x[j].y >> 8) & 0xFFu, first = (x[j].y >> 16) & 0xFFu, rem = x[j].y >> 24;
                 const bool live = i0 + j * kKbThreads + tid < cnt && off - 1u <= r;
                 const uint32_t lit = cls == CLS_EXIT_B ? next_lit[1] : next_lit[0];
