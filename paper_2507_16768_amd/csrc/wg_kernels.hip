@@ -321,10 +321,16 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
     const uint32_t xcd = blockIdx.x % nx, local = blockIdx.x / nx;
     const uint32_t local_wgs = (gridDim.x - xcd + nx - 1u) / nx;         // workgroups on this XCD
     const uint32_t my_groups = groups > xcd ? (groups - xcd + nx - 1u) / nx : 0u;
+    // Work item = (class table ci of the call's list, token group) with the table index in the
+    // upper part, so that which list entry a workgroup reads first depends on its place in the
+    // grid only: it is requested together with the length of the list, not after it.
     const uint64_t total = (uint64_t)n * my_groups;
+    const uint32_t ci_first = my_groups ? local / my_groups : 0u;
+    const uint32_t c_first = Cc.class_miss[ci_first < Cc.miss_cap ? ci_first : 0u];   // the list has miss_cap places
     for (uint64_t item = local; item < total; item += local_wgs) {
-        const uint32_t c = Cc.class_miss[(uint32_t)(item % n)];
-        const uint32_t g = (uint32_t)(item / n) * nx + xcd;
+        const uint32_t ci = (uint32_t)(item / my_groups);
+        const uint32_t c = item == local ? c_first : Cc.class_miss[ci];
+        const uint32_t g = (uint32_t)(item % my_groups) * nx + xcd;
         uint32_t part = 0;
 #pragma unroll
         for (uint32_t q = 1; q < kParts; q++) part += g * kScanGroup >= Vc.part_tok[q];
@@ -353,7 +359,7 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
         uint32_t *row_stay = Cc.class_rows + (size_t)(2u * c) * Cc.row_stride;
         uint32_t *row_end = row_stay + Cc.row_stride;
         uint32_t res[4], j[4];
-        unsigned long long bx[4], by[4];
+        unsigned long long bx[4], by[4], stay_bits[4], end_bits[4];
 #pragma unroll
         for (int s = 0; s < 4; s++) {
             res[s] = 0; j[s] = 0;
@@ -374,11 +380,7 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
             const bool is_long = L[s] - j[s] - 1u > kShortRem;
             bx[s] = __ballot(early && !is_long);
             by[s] = __ballot(early && is_long);
-            const uint32_t w0 = (tk[s] - lane) >> 5;
-            if (lane == 0 && tk[s] < V) {
-                row_stay[w0] = (uint32_t)bs; row_end[w0] = (uint32_t)be;
-                if (w0 + 1u < Vc.W) { row_stay[w0 + 1u] = (uint32_t)(bs >> 32); row_end[w0 + 1u] = (uint32_t)(be >> 32); }
-            }
+            stay_bits[s] = bs; end_bits[s] = be;
             if (lane == 0) { seg[0][wave * 4u + s] = (uint32_t)__popcll(bx[s]); seg[1][wave * 4u + s] = (uint32_t)__popcll(by[s]); }
         }
         __syncthreads();
@@ -417,6 +419,20 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
                 const uint32_t pos_c = seg_base[0][sh ? 0 : 1] + in_wg, pos_r = seg_base[1][sh ? 0 : 1] + in_wg;
                 out[sh ? pos_c : V - 1u - pos_c] = e;
                 out[sh ? out_lo + pos_r : out_hi - 1u - pos_r] = e;
+            }
+        }
+        // The two rows of the class index, two words per wavefront slice, last: a store issued
+        // between the classification of two slices would be waited for before the next slice's
+        // operands count as loaded.
+        if (lane < 4u) {
+            unsigned long long bs = stay_bits[0], be = end_bits[0];
+#pragma unroll
+            for (uint32_t s = 1; s < 4u; s++) { bs = lane == s ? stay_bits[s] : bs; be = lane == s ? end_bits[s] : be; }
+            const uint32_t t0 = g * kScanGroup + (wave * 4u + lane) * 64u;
+            if (t0 < V) {
+                const uint32_t w0 = t0 >> 5;
+                row_stay[w0] = (uint32_t)bs; row_end[w0] = (uint32_t)be;
+                if (w0 + 1u < Vc.W) { row_stay[w0 + 1u] = (uint32_t)(bs >> 32); row_end[w0 + 1u] = (uint32_t)(be >> 32); }
             }
         }
     }
