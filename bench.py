@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # WRITE_SIZE (profiles/bench_config4_hbm_traffic.txt; fetch scaled x2.000, write x1.000 by
 # the counters of a 512 MiB device copy).  They describe the kernels whose source hashes to
 # TRAFFIC_SOURCE_SHA256; with any other kernel source the field is reported as null.
-TRAFFIC_BYTES = {"class_scan": 4.08e6, "key_build": 9.14e6, "gather": 10.09e6, "apply": 57.71e6}
-TRAFFIC_SOURCE_SHA256 = "3a0ae35f51748d21e1b71e3b01decc679129ede70adbde29d957878114a58026"
+TRAFFIC_BYTES = {"class_scan": 4.08e6, "key_build": 9.11e6, "gather": 10.09e6, "apply": 57.70e6}
+TRAFFIC_SOURCE_SHA256 = "32574dd87c00dec43fb034b6a1a26df9a3c6f5f286ce9751c2d2b5c69845fc4a"
 
 
 def kernel_source_sha256():
