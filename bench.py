@@ -32,7 +32,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # the counters of a 512 MiB device copy).  They describe the kernels whose source hashes to
 # TRAFFIC_SOURCE_SHA256; with any other kernel source the field is reported as null.
 TRAFFIC_BYTES = {"class_scan": 4.08e6, "key_build": 9.11e6, "gather": 10.09e6, "apply": 57.70e6}
-TRAFFIC_SOURCE_SHA256 = "32574dd87c00dec43fb034b6a1a26df9a3c6f5f286ce9751c2d2b5c69845fc4a"
+TRAFFIC_SOURCE_SHA256 = "d4b12f84d89893740255247f439232577b6d1147f35b6779f0ecd72fc57c83a0"
 
 
 def kernel_source_sha256():

@@ -1,14 +1,16 @@
 // HIP kernels of the structured-decoding hot path for gfx950 (wave64).
 //
-//   lookup     : request state -> cache key, claims missing keys and class tables
-//   class_scan : every vocabulary token against one checkpoint's byte-class table
-//                (lane = token, table in LDS, 64-lane ballots pack the row words)
-//   key_build  : one workgroup per missing key assembles the row in LDS from the
-//                class index and the tokens that leave the state early
-//   gather     : cached row -> bitmask[b]
-//   apply    : logits <- -inf where the mask bit is 0
-//   advance  : per-request walk of the sampled token
-//   select   : harness sampler stand-in (k-th set bit of a row)
+//   lookup       : request state -> cache key, claims missing keys and class tables
+//                  (advance_lookup: after advancing the state by the sampled token)
+//   class_scan   : every vocabulary token against one checkpoint's byte-class table
+//                  (lane = token, table in LDS, 64-lane ballots pack the row words)
+//   key_build    : a workgroup assembles the row of a missing key (or its words for one token
+//                  range) in LDS from the class index and the tokens that leave the state early
+//   gather       : cached row -> bitmask[b]   (gather_apply: and -inf into the logits)
+//   apply        : logits <- -inf where the mask bit is 0
+//   masked_argmax: greedy choice under the mask, logits only read
+//   advance      : per-request walk of the sampled token
+//   select       : harness sampler stand-in (k-th set bit of a row)
 //
 // No MFMA anywhere: the path is byte matching and memory traffic.
 #include <hip/hip_runtime.h>
@@ -759,9 +761,10 @@ apply_vec_kernel(Elem *__restrict__ logits, int64_t row_stride, uint32_t V, uint
     }
 }
 
-// gather and apply in one pass, the last kernel of a whole decode step: thread = one mask byte
-// = 8 tokens, as in apply; the byte comes from where the request's mask lives, goes to the
-// caller's bitmask row, and its disallowed tokens are stored as -inf.
+// gather and apply in one pass, the last kernel of a whole decode step: a thread takes four
+// mask bytes (8 tokens each) 256 apart, loaded together so that finding where the request's
+// mask lives is paid once; each byte goes to the caller's bitmask row and its disallowed tokens
+// are stored as -inf.
 constexpr uint32_t kGaGroups = 4;          // mask bytes per thread of gather_apply, 256 apart
 template <typename Vec, int kVecs, typename Elem>
 __global__ void __launch_bounds__(256)
