@@ -572,6 +572,21 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
                 reinterpret_cast<uint32_t *>(hop_lut[w])[tid] =
                     reinterpret_cast<const uint32_t *>(T.classes + (size_t)me.hop[w].cls * 256u)[tid];
         if (tid == 0) queued = 0;
+        // The first pass of candidates is requested before the row is set up, so that the loads
+        // are under way while (a) runs: kKbPer per thread, plain 8-byte loads from clamped
+        // indexes (a load inside a lane-dependent branch would be waited for on the spot).
+        const global_u2 *ents2 = (const global_u2 *)(ents ? ents : Vc.lit_entries);
+        uint2 x[kKbPer];
+        auto request = [&](uint32_t i0) {
+#pragma unroll
+            for (uint32_t j = 0; j < kKbPer; j++) {
+                uint32_t i = i0 + j * kKbThreads + tid;
+                i = i < cnt ? i : (cnt ? cnt - 1u : 0u);
+                const global_u2 *src = ents2 + (i < n_front ? at_front + i : at_back + (i - n_front));
+                x[j] = uint2{src->x, src->y};
+            }
+        };
+        request(0);
         // (a)
         uint4 *row4 = reinterpret_cast<uint4 *>(row);
         if (!stay) {
@@ -594,25 +609,15 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
         }
         __syncthreads();
         // (b) The candidates, kKbThreads * kKbPer per pass.  (b1) filter: every candidate is
-        // looked at once, kKbPer per thread, all loaded before any is used (plain 8-byte loads
-        // from clamped indexes: a load inside a branch would be waited for on the spot).  One
-        // that ends with its exit byte is accepted at once, one whose next byte cannot start the
-        // literal that follows is dropped, the others wait in LDS for (b2) their walk -- so that
-        // the walks, each a chain of dependent loads, run densely packed instead of a few lanes of
-        // every wavefront holding the others up.
+        // looked at once.  One that ends with its exit byte is accepted at once, one whose next
+        // byte cannot start the literal that follows is dropped, the others wait in LDS for (b2)
+        // their walk -- so that the walks, each a chain of dependent loads, run densely packed
+        // instead of a few lanes of every wavefront holding the others up.
         constexpr uint32_t kAnyByte = 0x100u;        // no literal follows this exit
         const uint32_t next_lit[2] = {me.hop[0].kind == WG_KIND_LIT ? me.hop[0].lit : kAnyByte,
                                       me.hop[1].kind == WG_KIND_LIT ? me.hop[1].lit : kAnyByte};
-        const global_u2 *ents2 = (const global_u2 *)ents;
         for (uint32_t i0 = 0; i0 < cnt; i0 += kKbThreads * kKbPer) {
-            uint2 x[kKbPer];
-#pragma unroll
-            for (uint32_t j = 0; j < kKbPer; j++) {
-                uint32_t i = i0 + j * kKbThreads + tid;
-                i = i < cnt ? i : cnt - 1u;
-                const global_u2 *src = ents2 + (i < n_front ? at_front + i : at_back + (i - n_front));
-                x[j] = uint2{src->x, src->y};
-            }
+            if (i0) request(i0);
             uint32_t slot[kKbPer], in_wave = 0;               // place among the wavefront's candidates to walk
             uint32_t need = 0;                                   // bit j: x[j] has to be walked
 #pragma unroll
