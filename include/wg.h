@@ -37,6 +37,10 @@
  *     Calls on one handle must be
  *     ordered on one stream (or otherwise serialised by the caller); the mask
  *     cache of a handle is shared state.
+ *   - A vocabulary lives on the device that was current in wg_vocab_create, and
+ *     so does every handle compiled against it.  wg_compile, wg_add_instances
+ *     and wg_cache_resize make that device current; the per-step calls expect
+ *     the caller to have it current (their pointers and stream belong to it).
  */
 #ifndef WG_H
 #define WG_H

@@ -124,7 +124,9 @@ class Oracle:
         self.num_states = L.wgo_num_states(self.h)
 
     def __del__(self):
-        if getattr(self, "h", None):
+        # at interpreter shutdown the module's globals may already be gone: then the process
+        # ends anyway and the handle is left to it
+        if getattr(self, "h", None) and lib is not None:
             lib().wgo_destroy(self.h)
             self.h = None
 

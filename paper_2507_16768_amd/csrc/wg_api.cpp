@@ -178,7 +178,7 @@ int sync_table(wg_handle_s *h, hipStream_t s) {
         const uint32_t a = h->up_classes, n = n_classes - a;
         WG_HIP(hipMemcpyAsync(h->d_classes + (size_t)a * 256, t.classes.data() + (size_t)a * 256, (size_t)n * 256,
                               hipMemcpyHostToDevice, s));
-        for (uint32_t c = a; c < n_classes; c++) {
+        while (h->class_bufs.size() < n_classes) {           // (a call that failed half way left some)
             ExitEntry *buf = nullptr;
             // V slots for the list of the whole class table, V for the lists of its token ranges
             WG_HIP(hipMalloc(reinterpret_cast<void **>(&buf), 2u * (size_t)V * sizeof(ExitEntry)));

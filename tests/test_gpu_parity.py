@@ -109,6 +109,16 @@ def test_reduced_configs_every_step(torch_cuda, idx, V, B, steps):
     assert s["lookups"] == B * steps and s["builds"] == nkeys and 0 < s["hits"] <= B * steps - nkeys
 
 
+@pytest.mark.parametrize("seed", [1, 2, 3])
+@pytest.mark.parametrize("idx,V,B,steps", [(4, 6001, 10, 48), (5, 20011, 64, 24)])
+def test_reduced_configs_under_other_seeds(torch_cuda, seed, idx, V, B, steps):
+    """Other vocabularies, templates and token streams than the base seed's, through the
+    separate calls and through the fused advance + fill."""
+    for fused in (False, True):
+        w = ws.make_workload(idx, seed=seed, V=V, B=B, steps=steps)
+        _replay(torch_cuda, w, steps, check_logits_every=8, label="cfg%d-seed%d" % (idx, seed), fused=fused)
+
+
 @pytest.mark.parametrize("idx,B,steps", [(2, 64, 24), (3, 128, 16), (4, 256, 12), (5, 1024, 6)])
 def test_full_size_configs_sampled(torch_cuda, idx, B, steps):
     """Full V and B of configs 2-5; states every step, every distinct mask, logits on 2 steps."""
