@@ -65,6 +65,8 @@ def lib():
         L.wgo_fill_masks.argtypes = [C.c_void_p, C.POINTER(_Vocab), C.c_void_p, C.c_uint32, C.c_void_p]
         L.wgo_apply_mask.argtypes = [C.c_void_p, C.c_int, C.c_uint32, C.c_uint32, C.c_int64, C.c_void_p]
         L.wgo_masked_argmax.argtypes = [C.c_void_p, C.c_int, C.c_uint32, C.c_uint32, C.c_int64, C.c_void_p, C.c_void_p]
+        L.wgo_masked_topk.argtypes = [C.c_void_p, C.c_int, C.c_uint32, C.c_uint32, C.c_int64, C.c_void_p,
+                                      C.c_uint32, C.c_void_p, C.c_void_p]
         L.wgo_advance.argtypes = [C.c_void_p, C.POINTER(_Vocab), C.c_void_p, C.c_void_p, C.c_uint32]
         L.wgo_key_rem.restype = C.c_uint32
         L.wgo_key_rem.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32]
@@ -227,6 +229,21 @@ def masked_argmax(logits, bitmask):
     out = np.zeros(B, dtype=np.int32)
     lib().wgo_masked_argmax(logits.ctypes.data, dt, B, V, V, bm.ctypes.data, out.ctypes.data)
     return out
+
+
+def masked_topk(logits, bitmask, k):
+    """(int32 [B, k] token ids, [B, k] raw values of the logits' type): the k best allowed tokens
+    per row of a float32 array or a uint16 array of bfloat16 bits, best first; -1 / -inf when
+    a row allows fewer than k."""
+    assert logits.flags["C_CONTIGUOUS"] and logits.ndim == 2
+    B, V = logits.shape
+    bm = np.ascontiguousarray(bitmask, dtype=np.uint32)
+    assert bm.shape == (B, (V + 31) // 32)
+    dt = {np.dtype(np.float32): 0, np.dtype(np.uint16): 1}[logits.dtype]
+    ids = np.zeros((B, k), dtype=np.int32)
+    vals = np.zeros((B, k), dtype=logits.dtype)
+    lib().wgo_masked_topk(logits.ctypes.data, dt, B, V, V, bm.ctypes.data, int(k), ids.ctypes.data, vals.ctypes.data)
+    return ids, vals
 
 
 def select_bit(row, k):

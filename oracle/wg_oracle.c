@@ -727,6 +727,43 @@ void wgo_masked_argmax(const void *logits, int dtype, uint32_t B, uint32_t V, in
     }
 }
 
+/* The k best allowed tokens of every row, best first: the greedy choice above made k times,
+ * each time among the allowed tokens not chosen yet (so the order is: larger logit first, equal
+ * values by lower token id, NaNs after every number).  ids_out[b][r] = -1 and values_out[b][r]
+ * = the bit pattern of -inf once the row's allowed tokens are used up.  values_out holds raw
+ * elements of the logits' type. */
+void wgo_masked_topk(const void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
+                     const uint32_t *bitmask, uint32_t k, int32_t *ids_out, void *values_out)
+{
+    uint32_t W = (V + 31u) / 32u;
+    uint8_t *taken = (uint8_t *)malloc(V ? V : 1);
+    for (uint32_t b = 0; b < B; b++) {
+        memset(taken, 0, V);
+        for (uint32_t r = 0; r < k; r++) {
+            int64_t best = -1; double best_v = 0.0; int best_nan = 1;
+            for (uint32_t t = 0; t < V; t++) {
+                if (taken[t] || !((bitmask[(size_t)b * W + (t >> 5)] >> (t & 31)) & 1u)) continue;
+                double v = elem_value(logits, dtype, (int64_t)b * row_stride + t);
+                int is_nan = v != v;
+                int better;
+                if (best < 0) better = 1;
+                else if (best_nan) better = !is_nan;
+                else better = !is_nan && v > best_v;
+                if (better) { best = t; best_v = v; best_nan = is_nan; }
+            }
+            ids_out[(size_t)b * k + r] = (int32_t)best;
+            if (best >= 0) taken[best] = 1;
+            if (dtype == 0)
+                ((uint32_t *)values_out)[(size_t)b * k + r] =
+                    best >= 0 ? ((const uint32_t *)logits)[(int64_t)b * row_stride + best] : 0xFF800000u;
+            else
+                ((uint16_t *)values_out)[(size_t)b * k + r] =
+                    best >= 0 ? ((const uint16_t *)logits)[(int64_t)b * row_stride + best] : 0xFF80u;
+        }
+    }
+    free(taken);
+}
+
 /* states[b] <- state after tokens[b]; a rejected or out-of-range token gives ERROR. */
 void wgo_advance(const wgo_handle *h, const wgo_vocab *v, uint32_t *states /*[B][2]*/,
                  const int32_t *tokens, uint32_t B)

@@ -373,6 +373,61 @@ def test_masked_argmax_ties_nan_zero_and_empty_rows():
                            mask).tolist() == want
 
 
+# ---- the k best allowed tokens, against numpy's stable sort and hand-derived cases -----------
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("k", [1, 5, 64])
+def test_masked_topk_matches_a_stable_sort_on_ordinary_rows(dtype, k):
+    B, V = 5, 3000 + 5
+    W = (V + 31) // 32
+    x = ws.make_logits(6, B, V, 2.0)
+    m = ws.rng.draw(7, 9, np.arange(B * W)).astype(np.uint32).reshape(B, W)
+    m[:, -1] &= (1 << (V % 32)) - 1
+    bits = np.unpackbits(m.view(np.uint8).reshape(B, -1), axis=1, bitorder="little")[:, :V].astype(bool)
+    if dtype == "bf16":
+        raw = ws.to_bf16_bits(x)
+        val = (raw.astype(np.uint32) << 16).view(np.float32)          # many ties after rounding
+    else:
+        raw, val = x, x
+    ids, vals = O.masked_topk(raw, m, k)
+    for b in range(B):
+        allowed = np.nonzero(bits[b])[0]
+        order = allowed[np.argsort(-val[b, allowed].astype(np.float64), kind="stable")][:k]   # equal values: lower id first
+        assert ids[b].tolist() == order.tolist()
+        assert (vals[b] == raw[b, order]).all()
+    if k == 1:
+        assert (ids[:, 0] == O.masked_argmax(raw, m)).all()
+
+
+def test_masked_topk_ties_nan_zero_and_short_rows():
+    inf, nan = np.inf, np.nan
+    rows = np.array([
+        [1.0, 5.0, 5.0, 2.0, 5.0, 0.0, 0.0, 0.0],      # ties by id, then 3, then 0
+        [nan, nan, -inf, nan, 0.0, 0.0, 0.0, 0.0],     # -inf before the NaNs, NaNs by id
+        [-0.0, 0.0, -1.0, -0.0, 9.0, 9.0, 9.0, 9.0],   # the three zeros tie: by id
+        [3.0, 2.0, 1.0, 0.0, 0.0, 0.0, 0.0, 0.0],      # nothing allowed
+        [1.0, 2.0, 3.0, inf, 4.0, inf, 0.0, nan],      # +inf twice, NaN last
+    ], dtype=np.float32)
+    mask = np.array([[0b00011111], [0b00001111], [0b00001111], [0], [0b11111111]], dtype=np.uint32)
+    want = [[1, 2, 4, 3, 0, -1], [2, 0, 1, 3, -1, -1], [0, 1, 3, 2, -1, -1], [-1] * 6, [3, 5, 4, 2, 1, 0]]
+    ids, vals = O.masked_topk(rows, mask, 6)
+    assert ids.tolist() == want
+    ninf = np.array(-inf, dtype=np.float32).view(np.uint32)
+    for b in range(len(rows)):
+        for r in range(6):
+            t = want[b][r]
+            # the value is the element itself, bit for bit (a -0.0 stays -0.0, a NaN its payload)
+            assert vals[b, r].view(np.uint32) == (rows[b, t].view(np.uint32) if t >= 0 else ninf)
+    raw16 = ws.to_bf16_bits(np.nan_to_num(rows, nan=0.0)) | np.where(np.isnan(rows), 0x7FC0, 0).astype(np.uint16)
+    ids16, vals16 = O.masked_topk(raw16, mask, 6)
+    assert ids16.tolist() == want
+    assert vals16[3].tolist() == [0xFF80] * 6 and vals16[4, 0] == 0x7F80
+    # eight allowed tokens, k = 8: a permutation of them; k = 3: its first three
+    ids8, _ = O.masked_topk(rows[4:5], mask[4:5], 8)
+    assert ids8[0].tolist() == [3, 5, 4, 2, 1, 0, 6, 7]
+    assert O.masked_topk(rows[4:5], mask[4:5], 3)[0][0].tolist() == [3, 5, 4]
+
+
 # ---- P10: memoised trajectory masks equal fresh walks ---------------------------------------
 
 def test_trajectory_is_consistent_with_unmemoised_calls():
