@@ -376,6 +376,20 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     argmax_us = 1e3 * e0.elapsed_time(e1) / K
+    # the candidates of top-k sampling under the same masks (logits only read)
+    topk_k = 50
+    topk_ids = torch.empty((B, topk_k), dtype=torch.int32, device="cuda")
+    topk_vals = torch.empty((B, topk_k), dtype=tdt, device="cuda")
+    topk_work = torch.empty(wg.masked_topk_workspace(B, V, topk_k), dtype=torch.uint8, device="cuda")
+    for k in range(4):
+        wg.masked_topk(fresh[k & 3], mask, topk_ids, topk_vals, topk_work)
+    torch.cuda.synchronize()
+    e0.record()
+    for k in range(K):
+        wg.masked_topk(fresh[k & 3], mask, topk_ids, topk_vals, topk_work)
+    e1.record()
+    torch.cuda.synchronize()
+    topk_us = 1e3 * e0.elapsed_time(e1) / K
 
     # ---- algorithmic bytes per launch of each kernel ----
     sum_len = int(w.vocab.offsets[-1])
@@ -446,6 +460,9 @@ def main():
                    "cold_request_steps_per_s": B / sec_greedy_cold, "warm_request_steps_per_s": B / sec_greedy_warm,
                    "masked_argmax_us": argmax_us,
                    "masked_argmax_dense_read_GBs": B * (row_bytes + esz * V) / (argmax_us * 1e-6) / 1e9},
+        "topk": {"note": "wg_masked_topk on the masks of the last step, k = %d; logits are read, never written" % topk_k,
+                 "k": topk_k, "masked_topk_us": topk_us,
+                 "masked_topk_dense_read_GBs": B * (row_bytes + esz * V) / (topk_us * 1e-6) / 1e9},
         "host_setup": {"vocabulary_indexes_ms": vocab_ms, "compile_all_instances_ms": compile_ms,
                        "instances": len(w.texts),
                        "add_one_instance_us_median": float(np.median(join_us)) if join_us else None,

@@ -223,6 +223,23 @@ int wg_masked_argmax(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_
                      int64_t row_stride_elems, const uint32_t *d_bitmask, int32_t *d_tokens,
                      void *stream);
 
+/* wg_masked_topk: the candidates of top-k sampling taken under the mask, logits read once and
+ * never written (the step after mask application, fused with it like wg_masked_argmax).
+ * d_ids[b][r], r = 0 .. k-1: the allowed tokens of row b with the k largest logits, best
+ * first; equal logits (-0.0 equals +0.0) by lower token id, NaNs after every number (also after
+ * -inf).  d_values[b][r]: that token's logit, the raw element in the logits' dtype.  A row that
+ * allows fewer than k tokens ends with ids of -1 and values of -inf.  1 <= k <= 64;
+ * B <= 65535; ceil(V / 8192) * k <= 4096.  d_ids is int32 [B][k], d_values [B][k] of `dtype`.
+ * d_workspace: device memory of at least wg_masked_topk_workspace(B, V, k) bytes, 8-byte
+ * aligned, owned by the caller, overwritten by the call (it holds the best k of every 8,192
+ * tokens of a row between the call's two kernels); calls that share a workspace must not
+ * overlap.  Enqueues two kernels on `stream`; nothing is allocated. */
+uint64_t wg_masked_topk_workspace(uint32_t B, uint32_t V, uint32_t k);
+int wg_masked_topk(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V,
+                   int64_t row_stride_elems, const uint32_t *d_bitmask, uint32_t k,
+                   int32_t *d_ids, void *d_values, void *d_workspace, uint64_t workspace_bytes,
+                   void *stream);
+
 /* wg_advance: d_states[b] <- state after d_tokens[b] (state tracking, constant work per
  * symbol).  A token the state rejects, or a token id outside [0, V), gives
  * {WG_SID_ERROR, 0} and increments the handle's device error counter. */

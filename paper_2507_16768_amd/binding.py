@@ -57,7 +57,7 @@ EXPORTS = [
     "wg_last_error", "wg_select_tokens", "wg_profile_enable", "wg_profile_read", "wg_masked_argmax",
     "wg_add_instances", "wg_num_instances", "wg_cache_resize", "wg_table_add_instances",
     "wg_table_num_instances", "wg_advance_fill_masks", "wg_regex_to_template",
-    "wg_decode_step",
+    "wg_decode_step", "wg_masked_topk", "wg_masked_topk_workspace",
 ]
 
 
@@ -110,6 +110,9 @@ def load_library():
     L.wg_advance_fill_masks.argtypes = [vp, vp, vp, u32, vp, vp]
     L.wg_decode_step.argtypes = [vp, vp, vp, u32, vp, vp, C.c_int, i64, vp]
     L.wg_masked_argmax.argtypes = [vp, C.c_int, u32, u32, i64, vp, vp, vp]
+    L.wg_masked_topk_workspace.argtypes = [u32, u32, u32]
+    L.wg_masked_topk_workspace.restype = u64
+    L.wg_masked_topk.argtypes = [vp, C.c_int, u32, u32, i64, vp, u32, vp, vp, vp, u64, vp]
     L.wg_cache_clear.argtypes = [vp, vp]
     L.wg_cache_stats.argtypes = [vp, C.POINTER(_Stats)]
     L.wg_error_count.argtypes = [vp, C.POINTER(u64)]
@@ -374,6 +377,32 @@ def masked_argmax(logits, bitmask, tokens, stream=None):
     _check(load_library().wg_masked_argmax(C.c_void_p(logits.data_ptr()), dt, B, V, logits.stride(0),
                                            _dev(bitmask, torch.int32, "bitmask"),
                                            _dev(tokens, torch.int32, "tokens"), _stream_ptr(stream)))
+
+
+def masked_topk_workspace(B, V, k):
+    """wg_masked_topk_workspace: bytes of device workspace a wg_masked_topk call of this shape needs."""
+    return int(load_library().wg_masked_topk_workspace(B, V, k))
+
+
+def masked_topk(logits, bitmask, ids, values, workspace, stream=None):
+    """wg_masked_topk on a [B, V] float32 or bfloat16 device tensor: ids is int32 [B, k], values
+    [B, k] of the logits' dtype, workspace a device tensor of at least masked_topk_workspace bytes."""
+    import torch
+    if logits.dim() != 2 or not logits.is_cuda or logits.stride(1) != 1:
+        raise ValueError("logits must be a 2-d device tensor with unit inner stride")
+    dt = {torch.float32: F32, torch.bfloat16: BF16}.get(logits.dtype)
+    if dt is None:
+        raise ValueError("logits must be float32 or bfloat16")
+    B, V = logits.shape
+    if ids.dim() != 2 or ids.shape[0] != B or tuple(values.shape) != tuple(ids.shape):
+        raise ValueError("ids and values must be [B, k]")
+    if tuple(bitmask.shape) != (B, (V + 31) // 32):
+        raise ValueError("bitmask must be [B, ceil(V/32)]")
+    _check(load_library().wg_masked_topk(C.c_void_p(logits.data_ptr()), dt, B, V, logits.stride(0),
+                                         _dev(bitmask, torch.int32, "bitmask"), ids.shape[1],
+                                         _dev(ids, torch.int32, "ids"), _dev(values, logits.dtype, "values"),
+                                         _dev(workspace, None, "workspace"),
+                                         workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
 
 
 def select_tokens(bitmask, V, draws, tokens, stream=None):

@@ -583,6 +583,36 @@ int wg_masked_argmax(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_
     return WG_OK;
 }
 
+uint64_t wg_masked_topk_workspace(uint32_t B, uint32_t V, uint32_t k) {
+    const uint64_t n_slices = ((uint64_t)V + kTopkSlice - 1u) / kTopkSlice;
+    return (uint64_t)B * n_slices * k * sizeof(unsigned long long);
+}
+
+int wg_masked_topk(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V, int64_t row_stride_elems,
+                   const uint32_t *d_bitmask, uint32_t k, int32_t *d_ids, void *d_values,
+                   void *d_workspace, uint64_t workspace_bytes, void *stream) {
+    if (!d_logits || !d_bitmask || !d_ids || !d_values || !d_workspace)
+        return fail(WG_ERR_INVALID, "wg_masked_topk: null argument");
+    if (B == 0 || V == 0) return fail(WG_ERR_INVALID, "wg_masked_topk: empty batch or vocabulary");
+    if (dtype != WG_F32 && dtype != WG_BF16) return fail(WG_ERR_INVALID, "wg_masked_topk: unknown dtype");
+    if (row_stride_elems < (int64_t)V) return fail(WG_ERR_INVALID, "wg_masked_topk: row stride smaller than V");
+    if (B > kMaxBatch) return fail(WG_ERR_INVALID, "wg_masked_topk: B above 65535");
+    if (k == 0 || k > kTopkMax) return fail(WG_ERR_INVALID, "wg_masked_topk: k must be 1 .. 64");
+    const uint64_t n_slices = ((uint64_t)V + kTopkSlice - 1u) / kTopkSlice;
+    // the lists of a row's slices are merged in LDS, next to the merge's own 18 KB, within the
+    // 64 KB a kernel gets without asking
+    if (n_slices * k > kTopkMergeKeys)
+        return fail(WG_ERR_INVALID, "wg_masked_topk: ceil(V / 8192) * k above 4096 (the lists of a row do not fit the merge)");
+    if (workspace_bytes < wg_masked_topk_workspace(B, V, k))
+        return fail(WG_ERR_INVALID, "wg_masked_topk: the workspace needs " +
+                                        std::to_string(wg_masked_topk_workspace(B, V, k)) + " bytes");
+    if (reinterpret_cast<uintptr_t>(d_workspace) % 8 != 0)
+        return fail(WG_ERR_INVALID, "wg_masked_topk: the workspace must be 8-byte aligned");
+    WG_HIP(launch_masked_topk(d_logits, dtype, B, V, row_stride_elems, d_bitmask, k, d_ids, d_values,
+                              static_cast<unsigned long long *>(d_workspace), static_cast<hipStream_t>(stream)));
+    return WG_OK;
+}
+
 int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B, void *stream) {
     if (!h || !d_states || !d_tokens) return fail(WG_ERR_INVALID, "wg_advance: null argument");
     if (B == 0) return fail(WG_ERR_INVALID, "wg_advance: B is 0");

@@ -132,6 +132,14 @@ hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t
                         const uint32_t *bitmask, hipStream_t s);
 hipError_t launch_masked_argmax(const void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
                                 const uint32_t *bitmask, int32_t *tokens, hipStream_t s);
+// masked top-k: a workgroup ranks kTopkSlice tokens of a row; `lists` is the caller's workspace
+// of B * ceil(V / kTopkSlice) * k 64-bit keys
+constexpr uint32_t kTopkMax = 64;
+constexpr uint32_t kTopkSlice = 8192;
+constexpr uint32_t kTopkMergeKeys = 4096;    // most keys (slices * k) the merge of a row holds in LDS
+hipError_t launch_masked_topk(const void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
+                              const uint32_t *bitmask, uint32_t k, int32_t *ids, void *values,
+                              unsigned long long *lists, hipStream_t s);
 hipError_t launch_advance(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
                           wg_state_t *states, const int32_t *tokens, uint32_t B, hipStream_t s,
                           hipEvent_t *ev);

@@ -17,6 +17,7 @@
 #include <hip/hip_ext.h>
 
 #include "wg_device.h"
+#include "wg_order.h"
 
 namespace wg {
 
@@ -821,14 +822,6 @@ gather_apply_kernel(DeviceCache Cc, Elem *__restrict__ logits, int64_t row_strid
 // complement of the token id in the low half, so that a plain maximum prefers the larger logit
 // and then the lower id.  Key 0 means "no allowed token".  Workgroups merge their maxima with
 // one 64-bit atomic max per row; the workgroup of a row that finishes last writes the token id.
-__device__ __forceinline__ uint32_t order_key(uint32_t u)      // float bits -> orderable integer
-{
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0u;               // NaN
-    if ((u << 1) == 0u) u = 0u;                                    // -0.0 == +0.0
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float elem_float(uint32_t raw) { return __uint_as_float(raw); }
-__device__ __forceinline__ float elem_float(uint16_t raw) { return __uint_as_float((uint32_t)raw << 16); }  // bfloat16
 
 // Per-row merge area of masked argmax, shared by the workgroups of a row: the running maximum
 // of the keys and the number of workgroups that have reported.  File-scope device memory: all

@@ -705,6 +705,83 @@ def test_masked_argmax_matches_oracle(torch_cuda, dtype, V, stride_pad, offset):
     assert (H.host_logit_bits(view.contiguous()) == before).all()          # logits are only read
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("V,stride_pad,offset,k", [(151936, 0, 0, 50), (20000, 0, 0, 64), (4104, 8, 0, 64),
+                                                   (1000 + 13, 3, 0, 7), (4096, 0, 1, 1), (40, 0, 0, 64)])
+def test_masked_topk_matches_oracle(torch_cuda, dtype, V, stride_pad, offset, k):
+    """The k best allowed tokens per row, ids and raw values, bit for bit; several 8,192-token
+    slices and a ragged last one, rows with fewer than k allowed tokens, ties, NaNs, padded and
+    misaligned rows."""
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    B, W = 11, (V + 31) // 32
+    x = ws.make_logits(9, B, V, 2.0)
+    x[0, 3], x[0, 4], x[1, 5], x[2, :] = np.nan, np.inf, -0.0, np.nan
+    x[3, V // 3:V // 3 + 100] = 7.5                       # a long tie at the top
+    x[7, :] = -np.arange(V, dtype=np.float32) / 64.0       # descending: the best tokens sit in few threads
+    x[8, :] = 1.0                                          # all equal: the lowest ids win
+    x[9, :] = np.arange(V, dtype=np.float32) / 64.0        # ascending: the best tokens are the row's last
+    m = ws.rng.draw(10, 9, np.arange(B * W)).astype(np.uint32).reshape(B, W)
+    m[:, -1] &= (1 << (V % 32)) - 1 if V % 32 else 0xFFFFFFFF
+    m[4, :] = 0                                           # nothing allowed
+    m[5, :] = 0
+    m[5, W // 2] = 1 << 7                                 # a single allowed token
+    m[6, :] = 0xFFFFFFFF
+    m[6, -1] = m[0, -1] | 1
+    m[10, :] = 0
+    m[10, :: max(1, W // 5)] = 0x00010001                 # a dozen allowed tokens, far apart
+    m[:, -1] &= (1 << (V % 32)) - 1 if V % 32 else 0xFFFFFFFF             # no bits at or above V
+    host = x if dtype == "f32" else ws.to_bf16_bits(np.nan_to_num(x, nan=0.0)) | np.where(np.isnan(x), 0x7FC0, 0).astype(np.uint16)
+    want_ids, want_vals = O.masked_topk(host, m, k)
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    buf = torch.zeros(B * (V + stride_pad) + offset + 8, dtype=tdt, device="cuda")
+    view = buf[offset:offset + B * (V + stride_pad)].view(B, V + stride_pad)[:, :V]
+    view.copy_(H.dev_logits(host))
+    before = H.host_logit_bits(view.contiguous()).copy()
+    d_ids = torch.full((B, k), -7, dtype=torch.int32, device="cuda")
+    d_vals = torch.zeros((B, k), dtype=tdt, device="cuda")
+    work = torch.full((wg.masked_topk_workspace(B, V, k) // 8,), -1, dtype=torch.int64, device="cuda")
+    d_mask = torch.from_numpy(m.view(np.int32)).cuda()
+    for rep in range(2):                                   # the second call finds the workspace used
+        wg.masked_topk(view, d_mask, d_ids, d_vals, work)
+        assert (d_ids.cpu().numpy() == want_ids).all()
+        got_vals = H.host_logit_bits(d_vals)
+        assert (got_vals == (want_vals.view(np.uint32) if dtype == "f32" else want_vals)).all()
+    assert (want_ids[4] == -1).all() and want_ids[5].tolist() == [(W // 2) * 32 + 7] + [-1] * (k - 1)
+    assert (H.host_logit_bits(view.contiguous()) == before).all()          # logits are only read
+    d_tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    wg.masked_argmax(view, d_mask, d_tok)
+    assert (d_tok.cpu().numpy() == want_ids[:, 0]).all()                   # the best of the k is the greedy choice
+
+
+def test_masked_topk_under_the_masks_of_a_decode_batch(torch_cuda):
+    """Masks as the fill makes them (literal states with a handful of tokens, free-text Waits
+    with most of the vocabulary), config 4 reduced."""
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    w = ws.make_workload(4, V=33003 - 3, B=24, steps=30)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    cur = H.start_states(o, w)
+    toks, sts, _ = o.trajectory(cur, w.token_draws(30))
+    d_states = H.dev_states(cur)
+    d_mask = torch.empty((w.B, h.W), dtype=torch.int32, device="cuda")
+    k = 40
+    d_ids = torch.empty((w.B, k), dtype=torch.int32, device="cuda")
+    d_vals = torch.empty((w.B, k), dtype=torch.bfloat16, device="cuda")
+    work = torch.empty(wg.masked_topk_workspace(w.B, w.vocab.V, k), dtype=torch.uint8, device="cuda")
+    for step in range(30):
+        h.fill_masks(d_states, d_mask)
+        if step % 6 == 5:
+            host = H.logits_for(w, tag=step)
+            wg.masked_topk(H.dev_logits(host), d_mask, d_ids, d_vals, work)
+            want_ids, want_vals = O.masked_topk(host, o.fill_masks(cur), k)
+            assert (d_ids.cpu().numpy() == want_ids).all(), step
+            assert (H.host_logit_bits(d_vals) == want_vals).all(), step
+        h.advance(d_states, torch.from_numpy(toks[step]).cuda())
+        cur = o.advance(cur, toks[step])
+
+
 def test_greedy_decoding_without_writing_logits(torch_cuda):
     """fill -> masked_argmax -> advance equals fill -> apply -> argmax -> advance (config 1)."""
     torch = torch_cuda
@@ -766,5 +843,14 @@ def test_argument_errors_on_device_calls(torch_cuda):
     assert L.wg_decode_step(h._h, C.c_void_p(16), None, 0, C.c_void_p(16), C.c_void_p(16), 0, 2000, None) == -1
     assert L.wg_advance_fill_masks(h._h, C.c_void_p(16), None, 1, C.c_void_p(16), None) == -1
     assert L.wg_cache_resize(h._h, 0) == -1
+    p16, ws_bytes = C.c_void_p(16), L.wg_masked_topk_workspace(1, 2000, 8)
+    assert ws_bytes == 1 * 1 * 8 * 8 and L.wg_masked_topk_workspace(3, 8193, 64) == 3 * 2 * 64 * 8
+    assert L.wg_masked_topk(p16, 0, 1, 2000, 2000, p16, 0, p16, p16, p16, ws_bytes, None) == -1      # k = 0
+    assert L.wg_masked_topk(p16, 0, 1, 2000, 2000, p16, 65, p16, p16, p16, 1 << 20, None) == -1      # k > 64
+    assert L.wg_masked_topk(p16, 0, 1, 2000, 2000, p16, 8, p16, p16, p16, ws_bytes - 1, None) == -1  # workspace too small
+    assert b"workspace" in L.wg_last_error()
+    assert L.wg_masked_topk(p16, 0, 1, 2000, 2000, p16, 8, p16, p16, C.c_void_p(20), ws_bytes, None) == -1
+    assert L.wg_masked_topk(p16, 0, 1, 2000, 2000, p16, 8, p16, p16, None, ws_bytes, None) == -1
+    assert L.wg_masked_topk(p16, 0, 1, 8192 * 129, 8192 * 129, p16, 64, p16, p16, p16, 1 << 30, None) == -1
     with pytest.raises(wg.WgError):
         wg.Vocab(np.zeros(4, np.uint8), np.array([0, 3, 2], np.uint64), 0)
