@@ -9,10 +9,12 @@
 //
 //   topk_slice : a workgroup takes 8,192 tokens of one row, 32 per thread, held in registers.
 //                The k-th largest of the 256 thread maxima is a lower bound for the slice's
-//                k-th best key, so only keys at or above it can matter: at most 32 k of them
-//                (k threads reach the bound, 32 tokens each), in practice little more than
-//                k.  They go to LDS, are ranked by counting, and the best k leave for the
-//                workspace, best first.
+//                k-th best token, so only tokens at or above it can matter: in practice little
+//                more than k.  They go to LDS, are ranked by counting, and the best k leave
+//                for the workspace, best first.  The bound is first taken on the logits as
+//                floats (cheap, but any number of tokens may tie at it); if the candidates do
+//                not fit their list it is taken again on the rank keys themselves, where at
+//                most 32 k can reach it (k threads reach the bound, 32 tokens each).
 //   topk_merge : a workgroup per row does the same with the keys the row's slices left (a
 //                thread's share of them instead of a thread's tokens) and writes the ids and
 //                the raw values of the best k.
@@ -204,7 +206,6 @@ topk_slice_kernel(const Elem *__restrict__ logits, int64_t row_stride, uint32_t 
     for (uint32_t e = 0; e < kTkPer; e++) tm = __builtin_fmaxf(tm, x[e]);
     const uint32_t own32 = tm == tm ? (order_key(__float_as_uint(tm)) & 0xFFFFFF00u) | (255u - tid) : 0u;
     const uint32_t bound32 = kth_largest<uint32_t>(sh, own32, k);
-    // A candidate takes its place in the list with an LDS atomic of its own: there are few.
     uint32_t mine = 0;                                // bit e: token e of this thread is a candidate
     if (bound32) {
         const float bound_value = key_floor_value(bound32 & 0xFFFFFF00u);
@@ -234,8 +235,7 @@ topk_slice_kernel(const Elem *__restrict__ logits, int64_t row_stride, uint32_t 
             sh.cand[i] = ((unsigned long long)(order_key(__float_as_uint(elem_float(row[id]))) + 1u) << 32) | (0xFFFFFFFFu - id);
         }
         __syncthreads();
-    }
-    if (exact) {
+    } else {
         // Exact path: the thread maxima as rank keys.  k threads reach the k-th largest of them
         // and a thread holds 32 tokens, so at most 32 k tokens are at or above it: they always
         // fit the candidate list.  (Fewer than k threads with an allowed token: no bound, every
