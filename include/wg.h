@@ -224,7 +224,8 @@ int wg_masked_argmax(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_
                      void *stream);
 
 /* wg_masked_topk: the candidates of top-k sampling taken under the mask, logits read once and
- * never written (the step after mask application, fused with it like wg_masked_argmax).
+ * never written (the paper applies the mask to the logits before sampling, Introduction; this
+ * is the step after, fused with it like wg_masked_argmax).
  * d_ids[b][r], r = 0 .. k-1: the allowed tokens of row b with the k largest logits, best
  * first; equal logits (-0.0 equals +0.0) by lower token id, NaNs after every number (also after
  * -inf).  d_values[b][r]: that token's logit, the raw element in the logits' dtype.  A row that
@@ -233,7 +234,9 @@ int wg_masked_argmax(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_
  * d_workspace: device memory of at least wg_masked_topk_workspace(B, V, k) bytes, 8-byte
  * aligned, owned by the caller, overwritten by the call (it holds the best k of every 8,192
  * tokens of a row between the call's two kernels); calls that share a workspace must not
- * overlap.  Enqueues two kernels on `stream`; nothing is allocated. */
+ * overlap.  Mask bits at and above V must be zero, as wg_fill_masks leaves them.  Enqueues
+ * two kernels on `stream`; nothing is allocated.  Arguments outside the limits above, a null
+ * pointer or a workspace that is too small or misaligned give WG_ERR_INVALID and launch nothing. */
 uint64_t wg_masked_topk_workspace(uint32_t B, uint32_t V, uint32_t k);
 int wg_masked_topk(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V,
                    int64_t row_stride_elems, const uint32_t *d_bitmask, uint32_t k,
