@@ -61,7 +61,7 @@ struct MissEntry {
     uint32_t cls;                // WAIT / COND: class table id
     uint32_t lit, pad0;          // LIT: the byte (its first-byte buckets hold the candidates)
     uint32_t eos_next, next_a, next_b;
-    uint32_t slot;               // arena row of the result, or kNoSlot: build into the bitmask row of `req`
+    uint32_t slot;               // arena row of the result, or kNoSlot: only into the bitmask row of `req`
     uint32_t req;                // the request that claimed the key
     uint32_t pad[3];
     HopState hop[2];             // successors reached through exit A / exit B
@@ -93,6 +93,7 @@ constexpr uint32_t kNoSlot = 0xFFFFFFFFu;
 // kRefByKey | key for a mask built in this call (its tag then says where it went), or kNoKey
 // (no such state: a row of zeros).  Rows and keys stay below 2^30 and 2^31 - 1.
 constexpr uint32_t kRefByKey = 0x80000000u;
+constexpr uint32_t kRefSelf = 0xFFFFFFFEu;   // this request claimed the key: key_build writes its bitmask row itself
 constexpr uint32_t kMaxRows = 1u << 30, kMaxKeys = 0x7FFFFFFEu;
 constexpr uint32_t kMaxBatch = 65535u;     // request indexes fit the 16 bits of a tag (and grid.y)
 
@@ -111,7 +112,7 @@ struct DeviceCache {
     uint32_t *class_count;       // per class 2 + 2 * kParts counters (front, back of the class list, then of
                                  // each range), 128 bytes apart
     // per call
-    uint32_t *row_ref;           // [B] arena row of the request's mask, kRefByKey | key, or kNoKey
+    uint32_t *row_ref;           // [B] arena row of the request's mask, kRefByKey | key, kRefSelf, or kNoKey
     MissEntry *miss;             // [miss_cap]: deep keys from the front, plain keys from the back
     uint32_t miss_cap;           // the largest batch so far
     uint32_t *class_miss;        // [B]

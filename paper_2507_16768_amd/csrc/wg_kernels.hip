@@ -192,7 +192,7 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceVoc
             const bool this_call = t >= kTagClaim && ((t >> 16) & kTagLaunchMask) == launch;
             if (!hit && !this_call)
                 claimed = atomicCAS(&Cc.tags[key], t, kTagClaim | (launch << 16) | b) == t;
-            ref = hit ? (uint32_t)t : kRefByKey | key;
+            ref = hit ? (uint32_t)t : claimed ? kRefSelf : kRefByKey | key;
         }
         Cc.row_ref[b] = ref;
     }
@@ -661,15 +661,22 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
             if (ew >= 4u * q_lo && ew < 4u * q_hi) row[ew] |= 1u << ((uint32_t)Vc.eos_id & 31u);
         }
         __syncthreads();
-        // (c) to its arena row, or, if the arena had no row left, to the claimer's bitmask row
+        // (c) to its arena row (unless the arena had no row left) and to the bitmask row of the
+        // request that claimed the key, which the gather then leaves alone
         if (me.slot != kNoSlot) {
             uint4 *dst = reinterpret_cast<uint4 *>(Cc.arena + (size_t)me.slot * rs);
             for (uint32_t q = q_lo + tid; q < q_hi; q += kKbThreads) dst[q] = row4[q];
             if (tid == 0 && p0 == 0) Cc.tags[me.key] = ((unsigned long long)Cc.epoch << 32) | me.slot;
-        } else {
+        }
+        {
             uint32_t *dst = bitmask + (size_t)me.req * Vc.W;
-            const uint32_t w_hi = 4u * q_hi < Vc.W ? 4u * q_hi : Vc.W;
-            for (uint32_t w = 4u * q_lo + tid; w < w_hi; w += kKbThreads) dst[w] = row[w];
+            if (Vc.W % 4u == 0u && reinterpret_cast<uintptr_t>(bitmask) % 16u == 0u) {
+                uint4 *dst4 = reinterpret_cast<uint4 *>(dst);
+                for (uint32_t q = q_lo + tid; q < q_hi; q += kKbThreads) dst4[q] = row4[q];
+            } else {
+                const uint32_t w_hi = 4u * q_hi < Vc.W ? 4u * q_hi : Vc.W;
+                for (uint32_t w = 4u * q_lo + tid; w < w_hi; w += kKbThreads) dst[w] = row[w];
+            }
         }
         __syncthreads();
     }
@@ -690,20 +697,21 @@ __device__ __forceinline__ void close_fill(const DeviceCache &Cc)
     Cc.ctr->launch++;
 }
 
-// Where the mask of request b is: a row of the arena, the bitmask row of the request that
-// built it uncached (possibly b's own: then `in_place`), or nowhere (nullptr: a row of zeros).
+// Where the mask of request b is: a row of the arena, its own bitmask row already (`in_place`:
+// b claimed the key and key_build wrote the row there), the bitmask row of the request that
+// built it uncached, or nowhere (nullptr: a row of zeros).
 __device__ __forceinline__ const uint32_t *mask_source(const DeviceCache &Cc, uint32_t b, uint32_t B, uint32_t W,
                                                        const uint32_t *bitmask, bool &in_place)
 {
     in_place = false;
     const uint32_t ref = Cc.row_ref[b];
     if (ref < kRefByKey) return ref < Cc.cap_rows ? Cc.arena + (size_t)ref * Cc.row_stride : nullptr;   // cached before this call
+    if (ref == kRefSelf) { in_place = true; return bitmask + (size_t)b * W; }    // written by key_build
     if (ref == kNoKey) return nullptr;
     const unsigned long long t = Cc.tags[ref & ~kRefByKey];
     if ((uint32_t)(t >> 32) == Cc.epoch) return Cc.arena + (size_t)(uint32_t)t * Cc.row_stride;
     const uint32_t req = (uint32_t)(t & 0xFFFFu);
-    if (req == b) { in_place = true; return bitmask + (size_t)b * W; }          // built in place by key_build
-    return req < B ? bitmask + (size_t)req * W : nullptr;                        // built for another request of this call
+    return req < B ? bitmask + (size_t)req * W : nullptr;                        // built uncached for another request of this call
 }
 
 template <bool kVec>
