@@ -707,7 +707,8 @@ def test_masked_argmax_matches_oracle(torch_cuda, dtype, V, stride_pad, offset):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("V,stride_pad,offset,k", [(151936, 0, 0, 50), (20000, 0, 0, 64), (4104, 8, 0, 64),
-                                                   (1000 + 13, 3, 0, 7), (4096, 0, 1, 1), (40, 0, 0, 64)])
+                                                   (1000 + 13, 3, 0, 7), (4096, 0, 1, 1), (40, 0, 0, 64),
+                                                   (500000, 0, 0, 64)])    # 62 slices: near the merge's limit
 def test_masked_topk_matches_oracle(torch_cuda, dtype, V, stride_pad, offset, k):
     """The k best allowed tokens per row, ids and raw values, bit for bit; several 8,192-token
     slices and a ragged last one, rows with fewer than k allowed tokens, ties, NaNs, padded and
