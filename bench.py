@@ -102,6 +102,48 @@ def cpu_baseline(w, n_steps):
     return out
 
 
+def apply_patterns(B=256, V=151936, K=200):
+    """wg_apply_mask on bf16 logits under synthetic mask patterns: what a store that covers only
+    part of a 64-byte block costs.  Prints one line per pattern."""
+    import torch
+    import paper_2507_16768_amd as wg
+    wg.load_library()
+    W = (V + 31) // 32
+    ring = [torch.randn((B, V), device="cuda").to(torch.bfloat16) for _ in range(4)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(mask):
+        for k in range(8):
+            wg.apply_mask(ring[k & 3], mask)
+        torch.cuda.synchronize()
+        e0.record()
+        for k in range(K):
+            wg.apply_mask(ring[k & 3], mask)
+        e1.record()
+        torch.cuda.synchronize()
+        return 1e3 * e0.elapsed_time(e1) / K
+
+    def words(value):
+        return torch.full((B, W), value, dtype=torch.int64, device="cuda").to(torch.int32)
+
+    rows = torch.zeros((B, W), dtype=torch.int32, device="cuda")
+    rows[::2, :] = -1
+    halves = torch.zeros((B, W), dtype=torch.int32, device="cuda")
+    halves[:, ::2] = -1
+    cases = [("nothing disallowed (mask read only; the loop's launch rate)", words(-1)),
+             ("everything disallowed: 16-byte stores, every block written whole", words(0)),
+             ("every other row disallowed", rows),
+             ("every other 64-byte block disallowed", halves),
+             ("every other 16 bytes disallowed", words(0x00FF00FF)),
+             ("1 token of 32 disallowed: one 2-byte store per 64-byte block", words(-2)),
+             ("1 token of 8 disallowed", words(0xFEFEFEFE - (1 << 32))),
+             ("4 tokens of 8 disallowed, alternating", words(0x55555555)),
+             ("7 tokens of 8 disallowed", words(0x01010101))]
+    print("wg_apply_mask, B=%d, V=%d, bf16 (%.1f MB of logits), mean of %d launches" % (B, V, B * V * 2 / 1e6, K))
+    for name, mask in cases:
+        print("%-68s %6.2f us" % (name, timed(mask)), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -109,7 +151,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="workload index 1..5 (default: 4, mixed)")
     ap.add_argument("--cpu-steps", type=int, default=32, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--apply-patterns", action="store_true",
+                    help="instead of the benchmark: time wg_apply_mask under synthetic mask patterns")
     args = ap.parse_args()
+    if args.apply_patterns:
+        apply_patterns()
+        return
     if args.gpus != 1:
         print("bench.py measures one GPU; --gpus %d is not supported (the path shards by request or "
               "by vocabulary slice without collectives, so more GPUs add nothing to measure here)"
@@ -338,6 +385,13 @@ def main():
     torch.cuda.synchronize()
     apply_us = 1e3 * e0.elapsed_time(e1) / K
     kt_cold["apply_us"] = kt_warm["apply_us"] = apply_us
+    # The mask that loop applied, by groups of 32 tokens (one mask word; 64 bytes of bf16 logits):
+    # a group that is disallowed as a whole is written as full blocks; a store into a mixed one
+    # covers part of a block, which costs more than writing the block whole (--apply-patterns).
+    n_words = float(B * W)
+    words_full = (mask == 0).sum().item() / n_words
+    words_untouched = (mask == -1).sum().item() / n_words
+    words_mixed = 1.0 - words_full - words_untouched
 
     # ---- greedy variant of the step: fill, masked argmax (logits only read), advance ----
     greedy_tok = torch.empty(B, dtype=torch.int32, device="cuda")
@@ -454,7 +508,8 @@ def main():
         "kernels_GBs": {k: (v[0] / (v[1] * 1e-6) / 1e9 if v[1] > 0 else None) for k, v in per_kernel.items()},
         "apply": {"disallowed_fraction": disallowed_per_step / float(B * V),
                   "min_bytes_GBs": apply_min_bytes / (apply_us * 1e-6) / 1e9,
-                  "dense_equivalent_GBs": apply_dense_bytes / (apply_us * 1e-6) / 1e9},
+                  "dense_equivalent_GBs": apply_dense_bytes / (apply_us * 1e-6) / 1e9,
+                  "groups_of_32_tokens": {"untouched": words_untouched, "fully_disallowed": words_full, "mixed": words_mixed}},
         "greedy": {"note": "fill + wg_masked_argmax + advance; logits are read, never written",
                    "cold_ms_per_step": sec_greedy_cold * 1e3, "warm_ms_per_step": sec_greedy_warm * 1e3,
                    "cold_request_steps_per_s": B / sec_greedy_cold, "warm_request_steps_per_s": B / sec_greedy_warm,
