@@ -158,7 +158,7 @@ __device__ __forceinline__ LookupEnv lookup_env(const DeviceCache &Cc)
 
 // The lookup of request b in state (sid, aux); every lane of the wavefront calls it, `live`
 // says whether the lane has a request.
-__device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
+__device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceCache &Cc,
                                            const LookupEnv &env, uint32_t b, bool live, uint32_t sid, uint32_t aux)
 {
     const uint32_t lane = threadIdx.x & 63u;
@@ -260,14 +260,14 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceVoc
 }
 
 __global__ void __launch_bounds__(64)
-lookup_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, const wg_state_t *__restrict__ states, uint32_t B)
+lookup_kernel(DeviceTable T, DeviceCache Cc, const wg_state_t *__restrict__ states, uint32_t B)
 {
     const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
     const bool live = b < B;
     const LookupEnv env = lookup_env(Cc);
     uint32_t sid = 0, aux = 0;
     if (live) { sid = states[b].sid; aux = states[b].aux; }
-    lookup_one(T, Vc, Cc, env, b, live, sid, aux);
+    lookup_one(T, Cc, env, b, live, sid, aux);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -490,7 +490,6 @@ __device__ __forceinline__ bool walk_first_hop(const DeviceTable &T, const HopSt
 }
 
 constexpr uint32_t kKbThreads = 512;       // two workgroups per compute unit
-constexpr uint32_t kKbWaves = kKbThreads / 64u;
 constexpr uint32_t kKbPer = 12;            // candidates a thread filters per pass
 constexpr uint32_t kKbQueue = kKbThreads * kKbPer;   // candidates waiting for their walk: a whole pass fits (48 KB of LDS)
 typedef __attribute__((address_space(1))) uint2 global_u2;   // a load known to go to device memory
@@ -866,7 +865,7 @@ __device__ __forceinline__ void piece_max(const uint4 &v, uint32_t m, uint32_t, 
 template <typename Elem, bool kAligned>
 __global__ void __launch_bounds__(256)
 masked_argmax_kernel(const Elem *__restrict__ logits, int64_t row_stride, uint32_t V, uint32_t W,
-                     const uint32_t *__restrict__ bitmask, int32_t *__restrict__ tokens)
+                     const uint32_t *__restrict__ bitmask)
 {
     constexpr uint32_t kPer = 16 / sizeof(Elem);                  // tokens per 16-byte piece: 8 bf16, 4 fp32
     constexpr uint32_t kSubMask = (1u << kPer) - 1u;
@@ -1010,7 +1009,7 @@ advance_lookup_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, wg_state_t 
         advance_one(T, Vc, Cc, sid, aux, (int64_t)tokens[b]);
         states[b].sid = sid; states[b].aux = aux;
     }
-    lookup_one(T, Vc, Cc, env, b, live, sid, aux);
+    lookup_one(T, Cc, env, b, live, sid, aux);
 }
 
 // One block per row: d_tokens[b] = index of the (draw mod popcount)-th set bit.
@@ -1088,7 +1087,7 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
                        uint32_t n_cu, hipStream_t s, hipEvent_t *ev)
 {
     if (tokens) launch(advance_lookup_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s, ev, T, Vc, Cc, states, tokens, B);
-    else launch(lookup_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s, ev, T, Vc, Cc, static_cast<const wg_state_t *>(states), B);
+    else launch(lookup_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s, ev, T, Cc, static_cast<const wg_state_t *>(states), B);
     // the number of misses is only known on the device: both build kernels stride a fixed
     // grid over whatever the lookup queued and fall through when nothing is queued
     uint32_t groups = cdiv(Vc.V, kScanGroup);
@@ -1151,11 +1150,11 @@ hipError_t launch_masked_argmax(const void *logits, int dtype, uint32_t B, uint3
     const uint32_t pieces = cdiv(V, dtype == WG_F32 ? 4 : 8);
     dim3 g(cdiv(pieces, kArgmaxPieces * 256), B);
     if (dtype == WG_F32) {
-        if (vec_ok) masked_argmax_kernel<uint32_t, true><<<g, 256, 0, s>>>((const uint32_t *)logits, row_stride, V, W, bitmask, tokens);
-        else masked_argmax_kernel<uint32_t, false><<<g, 256, 0, s>>>((const uint32_t *)logits, row_stride, V, W, bitmask, tokens);
+        if (vec_ok) masked_argmax_kernel<uint32_t, true><<<g, 256, 0, s>>>((const uint32_t *)logits, row_stride, V, W, bitmask);
+        else masked_argmax_kernel<uint32_t, false><<<g, 256, 0, s>>>((const uint32_t *)logits, row_stride, V, W, bitmask);
     } else {
-        if (vec_ok) masked_argmax_kernel<uint16_t, true><<<g, 256, 0, s>>>((const uint16_t *)logits, row_stride, V, W, bitmask, tokens);
-        else masked_argmax_kernel<uint16_t, false><<<g, 256, 0, s>>>((const uint16_t *)logits, row_stride, V, W, bitmask, tokens);
+        if (vec_ok) masked_argmax_kernel<uint16_t, true><<<g, 256, 0, s>>>((const uint16_t *)logits, row_stride, V, W, bitmask);
+        else masked_argmax_kernel<uint16_t, false><<<g, 256, 0, s>>>((const uint16_t *)logits, row_stride, V, W, bitmask);
     }
     masked_argmax_finish_kernel<<<cdiv(B, 256), 256, 0, s>>>(tokens, B);
     return hipGetLastError();
