@@ -292,6 +292,33 @@ def main():
         return {"median_us": float(np.median(us)), "p10_us": float(np.percentile(us, 10)),
                 "p90_us": float(np.percentile(us, 90))}
 
+    # ---- spread of the calls of a step: an event after each call (their cost is inside the figures) ----
+    def parts_spread(cold):
+        states.copy_(start)
+        if cold:
+            h.cache_clear()
+        run(cold, 0, Wm)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
+        torch.cuda.synchronize()
+        for k in range(Wm, total):
+            e = ev[k - Wm]
+            if cold:
+                h.cache_clear()
+            e[0].record()
+            h.fill_masks(states, mask)
+            e[1].record()
+            wg.apply_mask(ring[k & 3], mask)
+            e[2].record()
+            h.advance(states, tokens[k])
+            e[3].record()
+        torch.cuda.synchronize()
+
+        def stats(a, b):
+            us = np.array([1e3 * e[a].elapsed_time(e[b]) for e in ev])
+            return {"median_us": float(np.median(us)), "p10_us": float(np.percentile(us, 10)),
+                    "p90_us": float(np.percentile(us, 90))}
+        return {"fill": stats(0, 1), "apply": stats(1, 2), "advance": stats(2, 3), "fill_apply": stats(0, 2)}
+
     # ---- the decode loop with advance and the next fill in one call ----
     def timed_fused(cold):
         def go(lo, hi):
@@ -334,6 +361,7 @@ def main():
     sec_warm = min(timed(False) for _ in range(3))
     kt_warm = kernel_times(False)
     spread_warm = step_spread(False)
+    parts_warm = parts_spread(False)
     assert h.cache_stats()["builds"] == pre["builds"], "a warm pass built a mask"
     # (the fused loop also fills for the state after the last step, which no pass before it saw)
     sec_fused_warm = min(timed_fused(False) for _ in range(3))
@@ -373,6 +401,7 @@ def main():
     entries_per_step = (s1["entries_walked"] - s0["entries_walked"]) / float(total)
     kt_cold = kernel_times(True)
     spread_cold = step_spread(True)
+    parts_cold = parts_spread(True)
     sec_fused_cold = timed_fused(True)
     sec_single_cold = timed_single(True)
     # apply is a single kernel outside the handle: time a back-to-back run of it
@@ -496,6 +525,9 @@ def main():
         "step_spread": {"note": "per-step times between events recorded at the step boundaries "
                                 "(fill + apply + advance, event cost included)",
                         "cold": spread_cold, "warm": spread_warm},
+        "calls_spread": {"note": "the calls of a step between events recorded after each (event cost and the host's "
+                                 "launch gaps included, so the parts add up to more than the step)",
+                         "cold": parts_cold, "warm": parts_warm},
         "single_call_step": {"note": "the same steps through wg_decode_step (advance + fill + apply, four launches)",
                              "cold_ms_per_step": sec_single_cold * 1e3, "warm_ms_per_step": sec_single_warm * 1e3,
                              "cold_request_steps_per_s": B / sec_single_cold,
