@@ -25,6 +25,24 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
 
 
+def test_topk_limits_are_checked_on_the_host_before_anything_is_launched():
+    """Workspace size and argument checks of wg_masked_topk (the pointers are never followed)."""
+    import ctypes as C
+    L = wg.load_library()
+    assert wg.masked_topk_workspace(1, 2000, 8) == 1 * 1 * 8 * 8
+    assert wg.masked_topk_workspace(3, 8193, 64) == 3 * 2 * 64 * 8
+    assert wg.masked_topk_workspace(256, 151936, 50) == 256 * 19 * 50 * 8
+    p, need = C.c_void_p(16), L.wg_masked_topk_workspace(1, 2000, 8)
+    bad = [dict(k=0), dict(k=65), dict(ws=need - 1), dict(work=C.c_void_p(20)), dict(work=None), dict(B=0),
+           dict(B=65536, ws=1 << 40), dict(dtype=2), dict(stride=1999), dict(V=8192 * 65, stride=8192 * 65, k=64, ws=1 << 40)]
+    for case in bad:
+        a = dict(B=1, V=2000, stride=2000, k=8, ws=need, work=p, dtype=0)
+        a.update(case)
+        rc = L.wg_masked_topk(p, a["dtype"], a["B"], a["V"], a["stride"], p, a["k"], p, p, a["work"], a["ws"], None)
+        assert rc == -1, case
+        assert L.wg_last_error().startswith(b"wg_masked_topk"), case
+
+
 def test_product_package_does_not_reach_for_the_oracle():
     pkg = os.path.join(ROOT, "paper_2507_16768_amd")
     for dirpath, _, files in os.walk(pkg):
