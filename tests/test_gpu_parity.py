@@ -2,6 +2,8 @@
 
 Masks, next states and masked logits are integer / bit-pattern results, so the bar is
 exact equality everywhere (no tolerance)."""
+import os
+
 import numpy as np
 import pytest
 
@@ -855,3 +857,13 @@ def test_argument_errors_on_device_calls(torch_cuda):
     assert L.wg_masked_topk(p16, 0, 1, 8192 * 129, 8192 * 129, p16, 64, p16, p16, p16, 1 << 30, None) == -1
     with pytest.raises(wg.WgError):
         wg.Vocab(np.zeros(4, np.uint8), np.array([0, 3, 2], np.uint64), 0)
+
+
+def test_plain_c_client_of_the_abi(torch_cuda):
+    """tests/abi/c_client.c: the calls of include/wg.h made from C (hipMalloc memory, a stream of its
+    own, no Python in between) and compared with the C oracle inside the same program."""
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "abi", "c_client")
+    assert os.path.exists(exe), "build it first: python -c 'import __graft_entry__ as g; g.build()'"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    assert r.returncode == 0 and r.stdout.strip().endswith("c_client ok"), (r.returncode, r.stdout[-500:], r.stderr[-1000:])

@@ -43,6 +43,16 @@ def test_topk_limits_are_checked_on_the_host_before_anything_is_launched():
         assert L.wg_last_error().startswith(b"wg_masked_topk"), case
 
 
+def test_plain_c_client_builds_against_the_header():
+    """tests/abi/c_client.c compiles as C11 against include/wg.h and links the library; without a
+    GPU it says so and leaves with status 77 (with one it runs the whole comparison)."""
+    import subprocess
+    import __graft_entry__ as g
+    exe = g.build_c_client()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert r.returncode in (0, 77), (r.returncode, r.stdout[-300:], r.stderr[-600:])
+
+
 def test_product_package_does_not_reach_for_the_oracle():
     pkg = os.path.join(ROOT, "paper_2507_16768_amd")
     for dirpath, _, files in os.walk(pkg):
