@@ -192,13 +192,20 @@ def main():
     # a request joining a running engine: one instance added to a live handle (host lowering of
     # its arguments into the cached static structure, upload of the new table slices)
     n_join = min(64, len(w.texts) - 1)
-    join_us = []
+    join_us, join_call_us = [], []
     if n_join > 0:
         hj = wg.Handle(w.texts[:1], w.args[:1] if w.args else None, vocab, flags=wg.EOS_RESTART)
         for i in range(1, n_join + 1):
             t0 = time.perf_counter()
             hj.add_instances(w.texts[i:i + 1], w.args[i:i + 1] if w.args else None)
             join_us.append((time.perf_counter() - t0) * 1e6)
+        # the same for the next instances of the list, with the Python lists turned into C arrays
+        # beforehand: the wg_add_instances call alone (lowering, upload of the new table slices)
+        for i in range(n_join + 1, min(2 * n_join + 1, len(w.texts))):
+            m = wg.marshal_templates(w.texts[i:i + 1], w.args[i:i + 1] if w.args else None)
+            t0 = time.perf_counter()
+            hj.add_instances(None, None, marshalled=m)
+            join_call_us.append((time.perf_counter() - t0) * 1e6)
         del hj
     W = h.W
     start = torch.from_numpy(np.ascontiguousarray(h.start_states[w.request_template]).view(np.int32).copy()).cuda()
@@ -553,7 +560,9 @@ def main():
         "host_setup": {"vocabulary_indexes_ms": vocab_ms, "compile_all_instances_ms": compile_ms,
                        "instances": len(w.texts),
                        "add_one_instance_us_median": float(np.median(join_us)) if join_us else None,
-                       "add_one_instance_us_p90": float(np.percentile(join_us, 90)) if join_us else None},
+                       "add_one_instance_us_p90": float(np.percentile(join_us, 90)) if join_us else None,
+                       "add_one_instance_call_only_us_median": float(np.median(join_call_us)) if join_call_us else None,
+                       "add_one_instance_call_only_us_p90": float(np.percentile(join_call_us, 90)) if join_call_us else None},
         "prepass": {"builds": pre["builds"], "lookups": pre["lookups"], "class_scans": pre["class_scans"]},
     }
     if cpu is not None:

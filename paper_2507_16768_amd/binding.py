@@ -152,6 +152,11 @@ def _marshal_templates(texts, args):
     return c_texts, c_args, n, keep
 
 
+def marshal_templates(texts, args):
+    """The C arrays of a list of templates and their argument sets, for add_instances(marshalled=...)."""
+    return _marshal_templates(texts, args)
+
+
 def _stream_ptr(stream):
     if stream is None:
         import torch
@@ -216,7 +221,7 @@ class Table:
         return r
 
     def __del__(self):
-        if getattr(self, "_t", None):
+        if getattr(self, "_t", None) and load_library is not None:   # (None: the interpreter is shutting down)
             load_library().wg_table_destroy(self._t)
             self._t = None
 
@@ -237,7 +242,7 @@ class Vocab:
         _check(L.wg_vocab_create(b.ctypes.data, o.ctypes.data, self.V, self.eos_id, C.byref(self._v)))
 
     def __del__(self):
-        if getattr(self, "_v", None):
+        if getattr(self, "_v", None) and load_library is not None:   # (None: the interpreter is shutting down)
             load_library().wg_vocab_destroy(self._v)
             self._v = None
 
@@ -302,10 +307,11 @@ class Handle:
             _dev(bitmask, torch.int32, "bitmask"), C.c_void_p(logits.data_ptr()), dt, logits.stride(0),
             _stream_ptr(stream)))
 
-    def add_instances(self, texts, args, stream=None):
-        """wg_add_instances: returns the start states [n, 2] of the new instances."""
+    def add_instances(self, texts, args, stream=None, marshalled=None):
+        """wg_add_instances: returns the start states [n, 2] of the new instances.  `marshalled`
+        takes what marshal_templates(texts, args) made beforehand instead of texts and args."""
         L = load_library()
-        c_texts, c_args, n, _keep = _marshal_templates(texts, args)
+        c_texts, c_args, n, _keep = marshalled if marshalled is not None else _marshal_templates(texts, args)
         starts = np.zeros((max(n, 1), 2), dtype=np.uint32)
         _check(L.wg_add_instances(self._h, c_texts, c_args, n, starts.ctypes.data, _stream_ptr(stream)))
         self.start_states = np.concatenate([self.start_states, starts[:n]])
@@ -340,7 +346,7 @@ class Handle:
         return n.value
 
     def __del__(self):
-        if getattr(self, "_h", None):
+        if getattr(self, "_h", None) and load_library is not None:   # (None: the interpreter is shutting down)
             load_library().wg_destroy(self._h)
             self._h = None
 

@@ -50,6 +50,8 @@ struct wg_handle_s {
     // class index storage: one buffer of V exit entries per class table in use, and the
     // device table of their addresses
     std::vector<ExitEntry *> class_bufs;
+    std::vector<ExitEntry *> class_slabs;             // what was allocated: class_bufs point into these
+    uint32_t slab_left = 0;                           // class buffers not handed out yet in the last slab
     ExitEntry **d_class_entries = nullptr;
     uint32_t max_batch = 0;
     uint32_t n_cu = 256;
@@ -166,27 +168,41 @@ int sync_table(wg_handle_s *h, hipStream_t s) {
         if (rc != WG_OK) return rc;
         h->cap_classes = nc;
     }
-    if (n_states > h->up_states) {
+    const bool new_states = n_states > h->up_states, new_classes = n_classes > h->up_classes;
+    if (new_states) {
         const uint32_t a = h->up_states, n = n_states - a;
         WG_HIP(hipMemcpyAsync(h->d_states + a, t.states.data() + a, n * sizeof(StateDesc), hipMemcpyHostToDevice, s));
         WG_HIP(hipMemcpyAsync(h->d_lit + a, t.lit.data() + a, n, hipMemcpyHostToDevice, s));
-        // the copies read pageable host memory that a later append may move
-        WG_HIP(hipStreamSynchronize(s));
-        h->up_states = n_states;
     }
-    if (n_classes > h->up_classes) {
+    if (new_classes) {
         const uint32_t a = h->up_classes, n = n_classes - a;
         WG_HIP(hipMemcpyAsync(h->d_classes + (size_t)a * 256, t.classes.data() + (size_t)a * 256, (size_t)n * 256,
                               hipMemcpyHostToDevice, s));
+        // Per class table: V slots for the list of the whole table, V for the lists of its token
+        // ranges.  The buffers are cut from slabs of several, so that an instance which brings
+        // one new table does not pay for a device allocation of its own.
+        const size_t per_class = 2u * (size_t)V;
         while (h->class_bufs.size() < n_classes) {           // (a call that failed half way left some)
-            ExitEntry *buf = nullptr;
-            // V slots for the list of the whole class table, V for the lists of its token ranges
-            WG_HIP(hipMalloc(reinterpret_cast<void **>(&buf), 2u * (size_t)V * sizeof(ExitEntry)));
-            h->class_bufs.push_back(buf);
+            if (h->slab_left == 0) {
+                const size_t missing = n_classes - h->class_bufs.size();
+                const uint32_t count = (uint32_t)(missing > 8 ? missing : 8);
+                ExitEntry *slab = nullptr;
+                WG_HIP(hipMalloc(reinterpret_cast<void **>(&slab), count * per_class * sizeof(ExitEntry)));
+                h->class_slabs.push_back(slab);
+                h->slab_left = count;
+                h->class_bufs.push_back(slab);
+            } else {
+                h->class_bufs.push_back(h->class_bufs.back() + per_class);
+            }
+            h->slab_left--;
         }
         WG_HIP(hipMemcpyAsync(h->d_class_entries + a, h->class_bufs.data() + a, n * sizeof(ExitEntry *),
                               hipMemcpyHostToDevice, s));
+    }
+    if (new_states || new_classes) {
+        // the copies read pageable host memory that a later append may move
         WG_HIP(hipStreamSynchronize(s));
+        h->up_states = n_states;
         h->up_classes = n_classes;
     }
     h->dt = DeviceTable{h->d_states, h->d_classes, h->d_lit, n_states, t.lmax, n_classes};
@@ -415,7 +431,7 @@ void wg_destroy(wg_handle_t h) {
     (void)hipFree(h->dc.row_ref); (void)hipFree(h->dc.miss); (void)hipFree(h->dc.class_miss);
     (void)hipFree(h->dc.class_built); (void)hipFree(h->dc.class_rows);
     (void)hipFree(h->d_class_entries); (void)hipFree(h->dc.class_count);
-    for (ExitEntry *b : h->class_bufs) (void)hipFree(b);
+    for (ExitEntry *b : h->class_slabs) (void)hipFree(b);
     for (auto *v : {&h->fill_events, &h->advance_events, &h->spare_events})
         for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
     delete h;
@@ -644,7 +660,7 @@ int wg_cache_stats(wg_handle_t h, wg_cache_stats_t *host_out) {
     host_out->rows_in_use = taken < h->dc.cap_rows ? taken : h->dc.cap_rows;
     const uint64_t row_bytes = (uint64_t)h->dc.row_stride * 4ull;
     host_out->arena_bytes = (uint64_t)h->dc.cap_rows * row_bytes +
-                            (uint64_t)h->class_bufs.size() * (2ull * h->vocab->dv.V * sizeof(ExitEntry)) +
+                            (uint64_t)(h->class_bufs.size() + h->slab_left) * (2ull * h->vocab->dv.V * sizeof(ExitEntry)) +
                             (uint64_t)h->cap_classes * 2ull * row_bytes;
     return WG_OK;
 }
