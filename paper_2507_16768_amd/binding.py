@@ -140,11 +140,11 @@ def _marshal_templates(texts, args):
         c_args = (_Args * max(n, 1))()
         for i, a in enumerate(args):
             names = [k.encode() for k in a]
-            vals = [np.frombuffer(bytes(v), dtype=np.uint8).copy() for v in a.values()]
+            vals = [bytes(v) for v in a.values()]         # the C side reads the bytes objects' own storage
             m = len(names)
             c_names = (C.c_char_p * max(m, 1))(*names)
             c_data = (C.POINTER(C.c_uint8) * max(m, 1))(
-                *[v.ctypes.data_as(C.POINTER(C.c_uint8)) for v in vals])
+                *[C.cast(C.c_char_p(v), C.POINTER(C.c_uint8)) for v in vals])
             c_lens = (C.c_uint64 * max(m, 1))(*[len(v) for v in vals])
             c_args[i] = _Args(m, c_names, c_data, c_lens)
             keep += [names, vals, c_names, c_data, c_lens]
