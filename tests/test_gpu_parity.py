@@ -864,6 +864,8 @@ def test_plain_c_client_of_the_abi(torch_cuda):
     own, no Python in between) and compared with the C oracle inside the same program."""
     import subprocess
     exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "abi", "c_client")
-    assert os.path.exists(exe), "build it first: python -c 'import __graft_entry__ as g; g.build()'"
+    if not os.path.exists(exe):                           # a second of gcc; the HIP library itself is never built here
+        import __graft_entry__ as g
+        g.build_c_client()
     r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
     assert r.returncode == 0 and r.stdout.strip().endswith("c_client ok"), (r.returncode, r.stdout[-500:], r.stderr[-1000:])
