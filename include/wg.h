@@ -30,10 +30,11 @@
  *     throws or exits; wg_last_error() describes the last failure on the
  *     calling thread.
  *   - The per-step calls only enqueue work on their stream: they do not
- *     synchronise, allocate or copy between host and device -- except that a
- *     fill with a batch larger than any before on the handle (and than 1,024)
- *     first grows the handle's per-call lists, which synchronises the device
- *     once.  wg_add_instances and wg_cache_resize say what they wait for.
+ *     synchronise, allocate or copy between host and device.  A handle has
+ *     room for batches of up to 1,024 requests per call; wg_reserve_batch
+ *     makes room for more (and synchronises), and a per-step call with a
+ *     larger batch than reserved fails with WG_ERR_INVALID and launches
+ *     nothing.  wg_add_instances and wg_cache_resize say what they wait for.
  *     Calls on one handle must be
  *     ordered on one stream (or otherwise serialised by the caller); the mask
  *     cache of a handle is shared state.
@@ -194,6 +195,15 @@ uint32_t wg_num_instances(wg_handle_t h);
  * (wg_cache_stats.uncached_builds counts them) until wg_cache_clear or a resize.  Synchronises
  * the device and clears the cache. */
 int wg_cache_resize(wg_handle_t h, uint32_t rows);
+
+/* wg_reserve_batch: room for calls with up to max_batch requests (1 .. 65535) in the handle's
+ * per-call lists (which request refers to which cache row, the keys and class tables a call has
+ * to build).  wg_compile reserves 1,024.  Only ever grows; when it grows, the device is
+ * synchronised and the lists are allocated anew, so a HIP graph recorded before has to be
+ * recorded again.  Call it at set-up, never between the steps of a decode loop: the per-step
+ * calls themselves never allocate and refuse a batch above the reservation. */
+int wg_reserve_batch(wg_handle_t h, uint32_t max_batch);
+uint32_t wg_max_batch(wg_handle_t h);       /* the current reservation */
 
 uint32_t wg_num_states(wg_handle_t h);
 uint32_t wg_mask_words(wg_handle_t h);      /* W = ceil(V/32) */

@@ -57,7 +57,7 @@ EXPORTS = [
     "wg_last_error", "wg_select_tokens", "wg_profile_enable", "wg_profile_read", "wg_masked_argmax",
     "wg_add_instances", "wg_num_instances", "wg_cache_resize", "wg_table_add_instances",
     "wg_table_num_instances", "wg_advance_fill_masks", "wg_regex_to_template",
-    "wg_decode_step", "wg_masked_topk", "wg_masked_topk_workspace",
+    "wg_decode_step", "wg_masked_topk", "wg_masked_topk_workspace", "wg_reserve_batch", "wg_max_batch",
 ]
 
 
@@ -100,6 +100,9 @@ def load_library():
     L.wg_num_instances.argtypes = [vp]
     L.wg_num_instances.restype = u32
     L.wg_cache_resize.argtypes = [vp, u32]
+    L.wg_reserve_batch.argtypes = [vp, u32]
+    L.wg_max_batch.argtypes = [vp]
+    L.wg_max_batch.restype = u32
     L.wg_num_states.argtypes = [vp]
     L.wg_num_states.restype = u32
     L.wg_mask_words.argtypes = [vp]
@@ -320,6 +323,12 @@ class Handle:
 
     def num_instances(self):
         return load_library().wg_num_instances(self._h)
+
+    def reserve_batch(self, max_batch):
+        _check(load_library().wg_reserve_batch(self._h, int(max_batch)))
+
+    def max_batch(self):
+        return load_library().wg_max_batch(self._h)
 
     def cache_resize(self, rows):
         _check(load_library().wg_cache_resize(self._h, int(rows)))

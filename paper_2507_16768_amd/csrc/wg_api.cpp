@@ -67,6 +67,8 @@ namespace {
 
 int fail(int code, const std::string &msg) { set_last_error(msg); return code; }
 
+constexpr uint32_t kDefaultBatch = 1024;   // requests per call a handle has room for after wg_compile
+
 #define WG_HIP(call)                                                                          \
     do {                                                                                      \
         hipError_t e_ = (call);                                                               \
@@ -92,24 +94,23 @@ hipEvent_t take_event(wg_handle_s *h) {
     return e;
 }
 
-int ensure_batch(wg_handle_s *h, uint32_t B) {
+// Room for the per-call lists of a batch of B requests.  Never called from the step path: the
+// device is synchronised and the lists are allocated anew.
+int reserve_batch(wg_handle_s *h, uint32_t B) {
     if (B <= h->max_batch) return WG_OK;
-    // grows only when a larger batch than ever before arrives (synchronises once)
-    uint32_t nb = h->max_batch ? h->max_batch : 1024;
-    while (nb < B) nb *= 2;
     WG_HIP(hipDeviceSynchronize());
     if (h->dc.row_ref) (void)hipFree(h->dc.row_ref);
     if (h->dc.miss) (void)hipFree(h->dc.miss);
     if (h->dc.class_miss) (void)hipFree(h->dc.class_miss);
     h->dc.row_ref = nullptr; h->dc.miss = nullptr; h->dc.class_miss = nullptr; h->max_batch = 0;
-    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.row_ref), nb * sizeof(uint32_t)));
-    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.miss), nb * sizeof(MissEntry)));
-    h->dc.miss_cap = nb;
-    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_miss), nb * sizeof(uint32_t)));
-    h->max_batch = nb;
+    h->dc.miss_cap = 0;
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.row_ref), B * sizeof(uint32_t)));
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.miss), B * sizeof(MissEntry)));
+    WG_HIP(hipMalloc(reinterpret_cast<void **>(&h->dc.class_miss), B * sizeof(uint32_t)));
+    h->dc.miss_cap = B;
+    h->max_batch = B;
     return WG_OK;
 }
-
 
 // Gives *p room for new_n elements, keeping the first keep_n and zero-filling the rest.
 template <class T> int regrow(T **p, size_t keep_n, size_t new_n, size_t pad_bytes = 0) {
@@ -492,7 +493,7 @@ int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_t
     WG_HIP(hipMemset(h->dc.ctr, 0, sizeof(Counters)));
     int rc = set_cache_rows(h.get(), (uint32_t)rows);
     if (rc == WG_OK) rc = sync_table(h.get(), nullptr);
-    if (rc == WG_OK) rc = ensure_batch(h.get(), 1024);
+    if (rc == WG_OK) rc = reserve_batch(h.get(), kDefaultBatch);
     if (rc != WG_OK) return rc;
     WG_HIP(hipDeviceSynchronize());
     if (start_states_out)
@@ -532,6 +533,15 @@ int wg_cache_resize(wg_handle_t h, uint32_t rows) {
     return next_generation(h, nullptr);
 }
 
+int wg_reserve_batch(wg_handle_t h, uint32_t max_batch) {
+    if (!h) return fail(WG_ERR_INVALID, "wg_reserve_batch: null handle");
+    if (max_batch == 0 || max_batch > kMaxBatch) return fail(WG_ERR_INVALID, "wg_reserve_batch: max_batch must be 1 .. 65535");
+    WG_HIP(hipSetDevice(h->vocab->device));
+    return reserve_batch(h, max_batch);
+}
+
+uint32_t wg_max_batch(wg_handle_t h) { return h ? h->max_batch : 0; }
+
 uint32_t wg_num_instances(wg_handle_t h) { return h ? (uint32_t)h->low.table.start.size() : 0; }
 uint32_t wg_num_states(wg_handle_t h) { return h ? h->dt.n_states : 0; }
 uint32_t wg_mask_words(wg_handle_t h) { return h ? h->vocab->dv.W : 0; }
@@ -543,8 +553,9 @@ int fill(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t 
          void *stream, const char *who, void *d_logits = nullptr, int dtype = WG_F32, int64_t logits_stride = 0) {
     if (B == 0) return fail(WG_ERR_INVALID, std::string(who) + ": B is 0");
     if (B > kMaxBatch) return fail(WG_ERR_INVALID, std::string(who) + ": B above 65535");
-    int rc = ensure_batch(h, B);
-    if (rc != WG_OK) return rc;
+    if (B > h->max_batch)
+        return fail(WG_ERR_INVALID, std::string(who) + ": B = " + std::to_string(B) + " is above the " +
+                                        std::to_string(h->max_batch) + " requests the handle has room for (wg_reserve_batch)");
     hipEvent_t ev[8];
     if (h->profiling) for (auto &e : ev) { e = take_event(h); h->fill_events.push_back(e); }
     WG_HIP(launch_fill(h->dt, h->vocab->dv, h->dc, d_states, d_tokens, B, d_bitmask, d_logits, dtype,

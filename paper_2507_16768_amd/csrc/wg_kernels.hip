@@ -16,6 +16,8 @@
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <mutex>
+
 #include "wg_device.h"
 #include "wg_order.h"
 
@@ -516,7 +518,7 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
     extern __shared__ __attribute__((aligned(16))) uint32_t row[];
     __shared__ __attribute__((aligned(16))) uint8_t hop_lut[2][256];
     __shared__ uint2 queue[kKbQueue];
-    __shared__ uint32_t queued;
+    __shared__ uint32_t queued[2];                   // candidates queued in the passes of even / odd number
     // The first quarter of the grid serves the deep items (front of the miss list), the rest the
     // plain ones (back), so that where a workgroup's first item lies does not depend on the counts.
     const uint32_t deep_wgs = gridDim.x / 4u ? gridDim.x / 4u : 1u;
@@ -571,11 +573,13 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
             if ((me.hop[w].kind == WG_KIND_WAIT || me.hop[w].kind == WG_KIND_COND) && tid < 64u)
                 reinterpret_cast<uint32_t *>(hop_lut[w])[tid] =
                     reinterpret_cast<const uint32_t *>(T.classes + (size_t)me.hop[w].cls * 256u)[tid];
-        if (tid == 0) queued = 0;
+        if (tid == 0) { queued[0] = 0; queued[1] = 0; }
         // The first pass of candidates is requested before the row is set up, so that the loads
         // are under way while (a) runs: kKbPer per thread, plain 8-byte loads from clamped
         // indexes (a load inside a lane-dependent branch would be waited for on the spot).
         const global_u2 *ents2 = (const global_u2 *)(ents ? ents : Vc.lit_entries);
+        // (an empty list still issues one load: from the first bucket entry, which always exists)
+        if (cnt == 0u) { ents2 = (const global_u2 *)Vc.lit_entries; at_back = 0u; }
         uint2 x[kKbPer];
         auto request = [&](uint32_t i0) {
 #pragma unroll
@@ -616,7 +620,8 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
         constexpr uint32_t kAnyByte = 0x100u;        // no literal follows this exit
         const uint32_t next_lit[2] = {me.hop[0].kind == WG_KIND_LIT ? me.hop[0].lit : kAnyByte,
                                       me.hop[1].kind == WG_KIND_LIT ? me.hop[1].lit : kAnyByte};
-        for (uint32_t i0 = 0; i0 < cnt; i0 += kKbThreads * kKbPer) {
+        uint32_t pass = 0;
+        for (uint32_t i0 = 0; i0 < cnt; i0 += kKbThreads * kKbPer, pass ^= 1u) {
             if (i0) request(i0);
             uint32_t slot[kKbPer], in_wave = 0;               // place among the wavefront's candidates to walk
             uint32_t need = 0;                                   // bit j: x[j] has to be walked
@@ -635,7 +640,7 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
             }
             if (in_wave) {                                       // one LDS atomic per wavefront and pass
                 uint32_t base = 0;
-                if (lane == 0) base = atomicAdd(&queued, in_wave);
+                if (lane == 0) base = atomicAdd(&queued[pass], in_wave);
                 base = __shfl(base, 0);
 #pragma unroll
                 for (uint32_t j = 0; j < kKbPer; j++)
@@ -643,7 +648,11 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
             }
             __syncthreads();
             // (b2) walk the queued candidates, one per thread and round
-            const uint32_t n_queued = queued;
+            // The other counter is cleared for the next pass here, between the two barriers of
+            // this pass: its last readers passed the barrier that ended the pass before, and its
+            // next writers wait behind the barrier that ends this one.
+            const uint32_t n_queued = queued[pass];
+            if (tid == 0) queued[pass ^ 1u] = 0;
             for (uint32_t i = tid; i < n_queued; i += kKbThreads) {
                 const uint2 q = queue[i];
                 ExitEntry e;
@@ -651,9 +660,7 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
                 if (walk_candidate(T, Vc, me, hop_lut, e, regs_ok)) atomicOr(&row[e.tok >> 5], 1u << (e.tok & 31u));
             }
             __syncthreads();
-            if (tid == 0) queued = 0;
         }
-        __syncthreads();
         if (tid == 0) atomicAdd(&Cc.ctr->entries_walked, (unsigned long long)cnt);
         if (tid == 0 && Vc.eos_id >= 0 && me.eos_next != WG_SID_ERROR) {
             const uint32_t ew = (uint32_t)Vc.eos_id >> 5;
@@ -1052,16 +1059,28 @@ select_kernel(const uint32_t *__restrict__ bitmask, uint32_t W, const uint64_t *
 static inline uint32_t cdiv(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
 
 // key_build keeps a whole mask row (dynamic LDS) next to its candidate queue and tables (static
-// LDS); together they may pass the 64 KB a kernel gets without asking.  Returns
+// LDS); together they may pass the 64 KB a kernel gets without asking.  The limit is a property
+// of the kernel on a device, shared by every handle of the process, so it is only ever raised: a
+// handle with short rows compiled later leaves the room a handle with long rows needs.  Returns
 // hipErrorInvalidValue when a row does not fit the 160 KB of a compute unit at all.
 hipError_t configure_kernels(uint32_t row_bytes)
 {
+    static std::mutex mu;
+    static uint32_t granted[64];                     // per device: dynamic LDS key_build may ask for
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
     hipFuncAttributes attr;
-    hipError_t e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(key_build_kernel));
+    e = hipFuncGetAttributes(&attr, reinterpret_cast<const void *>(key_build_kernel));
     if (e != hipSuccess) return e;
     if (attr.sharedSizeBytes + (size_t)row_bytes > 160u * 1024u) return hipErrorInvalidValue;
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(key_build_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)row_bytes);
+    std::lock_guard<std::mutex> lock(mu);
+    const uint32_t slot = (uint32_t)dev < 64u ? (uint32_t)dev : 63u;
+    if ((uint32_t)dev < 64u && row_bytes <= granted[slot]) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(key_build_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)row_bytes);
+    if (e == hipSuccess && (uint32_t)dev < 64u) granted[slot] = row_bytes;
+    return e;
 }
 
 // Launches on stream s; with a pair of events the kernel's own begin / end timestamps are

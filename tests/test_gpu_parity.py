@@ -351,6 +351,7 @@ def test_random_trees_every_state_every_token(torch_cuda, restart):
         h = wg.Handle(texts, None, gv, flags=wg.EOS_RESTART if restart else wg.EOS_STOP)
         st = _all_states(o)
         n_states += len(st)
+        h.reserve_batch(len(st))
         d_mask = torch.empty((len(st), h.W), dtype=torch.int32, device="cuda")
         h.fill_masks(H.dev_states(st), d_mask)
         want = o.fill_masks(st)
@@ -389,6 +390,7 @@ def test_templates_made_from_regular_expressions_run_on_the_device(torch_cuda):
     gv = wg.Vocab(vocab.bytes, vocab.offsets, vocab.eos_id)
     h = wg.Handle(texts, None, gv, flags=wg.EOS_STOP)
     st = _all_states(o)
+    h.reserve_batch(len(st))
     d_mask = torch.empty((len(st), h.W), dtype=torch.int32, device="cuda")
     h.fill_masks(H.dev_states(st), d_mask)
     assert (H.host_mask(d_mask) == o.fill_masks(st)).all()
@@ -486,26 +488,48 @@ def test_cache_cold_warm_and_duplicates(torch_cuda):
     assert s3["keys"] >= h.num_states and s3["arena_bytes"] >= s3["keys"] * h.W * 4
 
 
-def test_batch_larger_than_any_before_grows_the_call_scratch(torch_cuda):
-    """The per-call lists start at 1,024 entries; a batch of 2,500 makes the handle grow them."""
+def test_batch_above_the_reservation_is_refused_until_reserved(torch_cuda):
+    """A handle has room for 1,024 requests per call; a batch of 2,500 is refused by every
+    per-step call (nothing is launched, nothing allocated) until wg_reserve_batch made room."""
     torch = torch_cuda
+    import paper_2507_16768_amd as wg
     w = ws.make_workload(5, V=3001, B=2500, steps=3)
     o = H.make_oracle(w)
     v, h = H.make_gpu(w)
+    assert h.max_batch() == 1024
     cur = H.start_states(o, w)
     small = H.dev_states(cur[:100])
     d_small = torch.empty((100, h.W), dtype=torch.int32, device="cuda")
     h.fill_masks(small, d_small)                            # first a small call, then the large one
     toks, sts, _ = o.trajectory(cur, w.token_draws(3))
     d_states = H.dev_states(cur)
-    d_mask = torch.empty((2500, h.W), dtype=torch.int32, device="cuda")
+    d_mask = torch.full((2500, h.W), 0x13571357, dtype=torch.int32, device="cuda")
+    d_log = torch.zeros((2500, w.vocab.V), dtype=torch.float32, device="cuda")
+    d_tok = torch.from_numpy(toks[0]).cuda()
+    for call in (lambda: h.fill_masks(d_states, d_mask), lambda: h.advance_fill_masks(d_states, d_tok, d_mask),
+                 lambda: h.decode_step(d_states, None, d_mask, d_log)):
+        with pytest.raises(wg.WgError, match="wg_reserve_batch"):
+            call()
+    assert (H.host_mask(d_mask) == 0x13571357).all() and (H.host_states(d_states) == cur).all()
+    h.reserve_batch(2500)
+    assert h.max_batch() == 2500
+    h.reserve_batch(64)                                     # never shrinks
+    assert h.max_batch() == 2500
+    with pytest.raises(wg.WgError):
+        h.reserve_batch(0)
+    with pytest.raises(wg.WgError):
+        h.reserve_batch(65536)
     for k in range(3):
         h.fill_masks(d_states, d_mask)
         assert (H.host_mask(d_mask) == o.fill_masks(cur)).all(), k
         h.advance(d_states, torch.from_numpy(toks[k]).cuda())
         cur = o.advance(cur, toks[k])
         assert (H.host_states(d_states) == cur).all()
+    # the masks made before the reservation grew are still cached
+    before = h.cache_stats()["builds"]
+    h.fill_masks(small, d_small)
     assert (H.host_mask(d_small) == o.fill_masks(H.start_states(o, w)[:100])).all()
+    assert h.cache_stats()["builds"] == before
 
 
 def _pick_tokens(o_rows, draws):
