@@ -253,6 +253,23 @@ int wg_masked_topk(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t 
                    int32_t *d_ids, void *d_values, void *d_workspace, uint64_t workspace_bytes,
                    void *stream);
 
+/* wg_masked_topk_static: wg_masked_topk for callers that cannot allocate device memory, not
+ * even a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, limits and results as wg_masked_topk, except that the lists between
+ * its two kernels live in a device array inside the library (4 MiB per GPU, held until the
+ * process ends; wg_masked_topk_static_capacity() returns its size in bytes), so a call needs
+ * B * ceil(V / 8192) * k * 8 <= 4,194,304 (B = 256, V = 151,936, k = 64 takes 2.5 MB); anything
+ * larger gives WG_ERR_INVALID and launches nothing.  The call allocates and frees nothing and
+ * enqueues two kernels on `stream`; the array's address on the current device is asked of the
+ * HIP runtime once (by wg_vocab_create on that device, else by the first call).  Every call on a
+ * GPU uses that GPU's one array: calls that overlap on one GPU (two streams, two threads) race;
+ * order them on one stream.  Nothing has to be cleared between calls: the first kernel writes
+ * every key the second reads. */
+uint64_t wg_masked_topk_static_capacity(void);
+int wg_masked_topk_static(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V,
+                          int64_t row_stride_elems, const uint32_t *d_bitmask, uint32_t k,
+                          int32_t *d_ids, void *d_values, void *stream);
+
 /* wg_advance: d_states[b] <- state after d_tokens[b] (state tracking, constant work per
  * symbol).  A token the state rejects, or a token id outside [0, V), gives
  * {WG_SID_ERROR, 0} and increments the handle's device error counter. */

@@ -4,7 +4,7 @@ device-resident cache, logit masking, state advance) behind a small C ABI.
 `binding` wraps the shared library one-to-one; it marshals arguments and nothing else.
 """
 from .binding import (  # noqa: F401
-    WgError, Vocab, Handle, Table, apply_mask, masked_argmax, masked_topk, masked_topk_workspace, select_tokens, regex_to_template, marshal_templates,
+    WgError, Vocab, Handle, Table, apply_mask, masked_argmax, masked_topk, masked_topk_workspace, masked_topk_static, masked_topk_static_capacity, select_tokens, regex_to_template, marshal_templates,
     load_library, library_path,
     F32, BF16, EOS_STOP, EOS_RESTART, SID_FINAL, SID_ERROR,
 )

@@ -58,6 +58,7 @@ EXPORTS = [
     "wg_add_instances", "wg_num_instances", "wg_cache_resize", "wg_table_add_instances",
     "wg_table_num_instances", "wg_advance_fill_masks", "wg_regex_to_template",
     "wg_decode_step", "wg_masked_topk", "wg_masked_topk_workspace", "wg_reserve_batch", "wg_max_batch",
+    "wg_masked_topk_static", "wg_masked_topk_static_capacity",
 ]
 
 
@@ -116,6 +117,9 @@ def load_library():
     L.wg_masked_topk_workspace.argtypes = [u32, u32, u32]
     L.wg_masked_topk_workspace.restype = u64
     L.wg_masked_topk.argtypes = [vp, C.c_int, u32, u32, i64, vp, u32, vp, vp, vp, u64, vp]
+    L.wg_masked_topk_static_capacity.argtypes = []
+    L.wg_masked_topk_static_capacity.restype = u64
+    L.wg_masked_topk_static.argtypes = [vp, C.c_int, u32, u32, i64, vp, u32, vp, vp, vp]
     L.wg_cache_clear.argtypes = [vp, vp]
     L.wg_cache_stats.argtypes = [vp, C.POINTER(_Stats)]
     L.wg_error_count.argtypes = [vp, C.POINTER(u64)]
@@ -418,6 +422,30 @@ def masked_topk(logits, bitmask, ids, values, workspace, stream=None):
                                          _dev(ids, torch.int32, "ids"), _dev(values, logits.dtype, "values"),
                                          _dev(workspace, None, "workspace"),
                                          workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+
+
+def masked_topk_static_capacity():
+    """wg_masked_topk_static_capacity: bytes of lists the library holds per GPU."""
+    return int(load_library().wg_masked_topk_static_capacity())
+
+
+def masked_topk_static(logits, bitmask, ids, values, stream=None):
+    """wg_masked_topk_static: wg_masked_topk with the library's own workspace (nothing allocated)."""
+    import torch
+    if logits.dim() != 2 or not logits.is_cuda or logits.stride(1) != 1:
+        raise ValueError("logits must be a 2-d device tensor with unit inner stride")
+    dt = {torch.float32: F32, torch.bfloat16: BF16}.get(logits.dtype)
+    if dt is None:
+        raise ValueError("logits must be float32 or bfloat16")
+    B, V = logits.shape
+    if ids.dim() != 2 or ids.shape[0] != B or tuple(values.shape) != tuple(ids.shape):
+        raise ValueError("ids and values must be [B, k]")
+    if tuple(bitmask.shape) != (B, (V + 31) // 32):
+        raise ValueError("bitmask must be [B, ceil(V/32)]")
+    _check(load_library().wg_masked_topk_static(C.c_void_p(logits.data_ptr()), dt, B, V, logits.stride(0),
+                                                _dev(bitmask, torch.int32, "bitmask"), ids.shape[1],
+                                                _dev(ids, torch.int32, "ids"), _dev(values, logits.dtype, "values"),
+                                                _stream_ptr(stream)))
 
 
 def select_tokens(bitmask, V, draws, tokens, stream=None):

@@ -263,6 +263,12 @@ int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uin
     std::unique_ptr<wg_vocab_s> v(new (std::nothrow) wg_vocab_s);
     if (!v) return fail(WG_ERR_NOMEM, "wg_vocab_create: out of host memory");
     WG_HIP(hipGetDevice(&v->device));
+    {
+        // set-up time on this device: the address of the library's own top-k workspace is asked
+        // for here, so that wg_masked_topk_static finds it known (it asks itself otherwise)
+        unsigned long long *unused = nullptr;
+        (void)static_topk_scratch(&unused);
+    }
     const uint32_t W = (V + 31u) / 32u, rs = (W + 3u) & ~3u;
     const uint32_t n_chunks = (lmax + 7u) / 8u;
     // Static indexes of the vocabulary (they depend on the token bytes only):
@@ -637,6 +643,32 @@ int wg_masked_topk(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t 
         return fail(WG_ERR_INVALID, "wg_masked_topk: the workspace must be 8-byte aligned");
     WG_HIP(launch_masked_topk(d_logits, dtype, B, V, row_stride_elems, d_bitmask, k, d_ids, d_values,
                               static_cast<unsigned long long *>(d_workspace), static_cast<hipStream_t>(stream)));
+    return WG_OK;
+}
+
+uint64_t wg_masked_topk_static_capacity(void) { return kTopkStaticKeys * sizeof(unsigned long long); }
+
+int wg_masked_topk_static(const void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V, int64_t row_stride_elems,
+                          const uint32_t *d_bitmask, uint32_t k, int32_t *d_ids, void *d_values, void *stream) {
+    if (!d_logits || !d_bitmask || !d_ids || !d_values)
+        return fail(WG_ERR_INVALID, "wg_masked_topk_static: null argument");
+    if (B == 0 || V == 0) return fail(WG_ERR_INVALID, "wg_masked_topk_static: empty batch or vocabulary");
+    if (dtype != WG_F32 && dtype != WG_BF16) return fail(WG_ERR_INVALID, "wg_masked_topk_static: unknown dtype");
+    if (row_stride_elems < (int64_t)V) return fail(WG_ERR_INVALID, "wg_masked_topk_static: row stride smaller than V");
+    if (B > kMaxBatch) return fail(WG_ERR_INVALID, "wg_masked_topk_static: B above 65535");
+    if (k == 0 || k > kTopkMax) return fail(WG_ERR_INVALID, "wg_masked_topk_static: k must be 1 .. 64");
+    const uint64_t n_slices = ((uint64_t)V + kTopkSlice - 1u) / kTopkSlice;
+    if (n_slices * k > kTopkMergeKeys)
+        return fail(WG_ERR_INVALID, "wg_masked_topk_static: ceil(V / 8192) * k above 4096 (the lists of a row do not fit the merge)");
+    const uint64_t need = wg_masked_topk_workspace(B, V, k);
+    if (need > wg_masked_topk_static_capacity())
+        return fail(WG_ERR_INVALID, "wg_masked_topk_static: B * ceil(V / 8192) * k * 8 = " + std::to_string(need) +
+                                        " bytes of lists, above the " + std::to_string(wg_masked_topk_static_capacity()) +
+                                        " the library holds per GPU (use wg_masked_topk with a workspace)");
+    unsigned long long *lists = nullptr;
+    WG_HIP(static_topk_scratch(&lists));
+    WG_HIP(launch_masked_topk(d_logits, dtype, B, V, row_stride_elems, d_bitmask, k, d_ids, d_values, lists,
+                              static_cast<hipStream_t>(stream)));
     return WG_OK;
 }
 

@@ -141,6 +141,10 @@ constexpr uint32_t kTopkMergeKeys = 4096;    // most keys (slices * k) the merge
 hipError_t launch_masked_topk(const void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
                               const uint32_t *bitmask, uint32_t k, int32_t *ids, void *values,
                               unsigned long long *lists, hipStream_t s);
+// wg_masked_topk_static keeps its lists in a file-scope device array of this many 64-bit keys
+// (4 MiB per GPU); static_topk_scratch gives the array's address on the current device.
+constexpr uint64_t kTopkStaticKeys = 1ull << 19;
+hipError_t static_topk_scratch(unsigned long long **out);
 hipError_t launch_advance(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
                           wg_state_t *states, const int32_t *tokens, uint32_t B, hipStream_t s,
                           hipEvent_t *ev);

@@ -23,10 +23,19 @@
 // value's place among all 256 is its lane plus a binary search in each of the other three lists.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "wg_device.h"
 #include "wg_order.h"
 
 namespace wg {
+
+// The workspace of wg_masked_topk_static: what wg_masked_topk takes from its caller, held by the
+// library instead, for callers that cannot allocate.  One copy per GPU the library runs on, for
+// the life of the process.  topk_slice writes every key of a call's lists before topk_merge reads
+// them, so nothing has to be cleared between calls.  In host code the array's name is a stand-in
+// only; its address on the current device comes from static_topk_scratch().
+static __device__ __align__(256) unsigned long long scratch[kTopkStaticKeys];
 
 constexpr uint32_t kTkThreads = 256;
 constexpr uint32_t kTkPer = kTopkSlice / kTkThreads;     // tokens per thread
@@ -302,6 +311,28 @@ topk_merge_kernel(const Elem *__restrict__ logits, int64_t row_stride, uint32_t 
         ids[(size_t)b * k + r] = -1;
         values[(size_t)b * k + r] = ninf;
     }
+}
+
+// The address of `scratch` on the current device, asked of the runtime once per device.
+hipError_t static_topk_scratch(unsigned long long **out)
+{
+    constexpr int kDevices = 64;
+    static std::mutex mu;
+    static unsigned long long *ptr[kDevices];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev] = static_cast<unsigned long long *>(p);
+    }
+    *out = ptr[dev];
+    return hipSuccess;
 }
 
 hipError_t launch_masked_topk(const void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
