@@ -7,7 +7,10 @@ gather (wg_fill_masks), logit masking (wg_apply_mask) and state advance
 V=151,936 tokens, bf16 logits, one template instance per request) on seeded
 synthetic inputs.  "cold" clears the mask cache before every step, so every
 distinct state key of the batch is rebuilt; "warm" replays the same trajectory with
-every mask cached.  The headline value is the cold rate.
+every mask cached.  The headline value is the cold rate: the median over several passes
+of the K timed steps, taken after the GPU has been kept busy long enough for its clocks to
+settle, so that a short run reads the same as a long one.  The timed steps are always the
+same window of the trajectory (it starts at step WINDOW_START), whatever K is.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 
@@ -32,6 +35,9 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # the counters of a 512 MiB device copy).  They describe the kernels whose source hashes to
 # TRAFFIC_SOURCE_SHA256; with any other kernel source the field is reported as null.
 TRAFFIC_BYTES = {"class_scan": 4.09e6, "key_build": 13.99e6, "gather": 0.04e6, "apply": 57.70e6}
+WINDOW_START = 64              # first timed step of the trajectory (the warm-up steps come right before it)
+N_PASSES = 5                   # timed passes per figure; the median is reported
+RAMP_SECONDS = 0.08            # GPU work done before timing, for the clocks to settle
 TRAFFIC_SOURCE_SHA256 = "70e63cf2bd68caa2bce1230b891b3e50fa1ca58b792890c22e0d07cab9d494f8"
 
 
@@ -144,6 +150,17 @@ def apply_patterns(B=256, V=151936, K=200):
         print("%-68s %6.2f us" % (name, timed(mask)), flush=True)
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -151,6 +168,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=4, help="workload index 1..5 (default: 4, mixed)")
     ap.add_argument("--cpu-steps", type=int, default=32, help="oracle steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--brief", action="store_true",
+                    help="only the separate-call and wg_decode_step timings and the kernel table (for profiler runs)")
     ap.add_argument("--apply-patterns", action="store_true",
                     help="instead of the benchmark: time wg_apply_mask under synthetic mask patterns")
     args = ap.parse_args()
@@ -178,7 +197,8 @@ def main():
     wg.load_library()
     torch.cuda.set_device(0)
     K, Wm = args.steps, args.warmup
-    total = K + Wm
+    k0 = max(WINDOW_START, Wm)          # first timed step; steps k0 - Wm .. k0 - 1 are the warm-up
+    total = k0 + K
     B, V = w.B, w.vocab.V
     tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
     esz = 4 if w.dtype == "f32" else 2
@@ -189,9 +209,10 @@ def main():
     t0 = time.perf_counter()
     h = wg.Handle(w.texts, w.args, vocab, flags=wg.EOS_RESTART)
     compile_ms = (time.perf_counter() - t0) * 1e3
+    h.reserve_batch(B)
     # a request joining a running engine: one instance added to a live handle (host lowering of
     # its arguments into the cached static structure, upload of the new table slices)
-    n_join = min(64, len(w.texts) - 1)
+    n_join = 0 if args.brief else min(64, len(w.texts) - 1)
     join_us, join_call_us = [], []
     if n_join > 0:
         hj = wg.Handle(w.texts[:1], w.args[:1] if w.args else None, vocab, flags=wg.EOS_RESTART)
@@ -210,54 +231,48 @@ def main():
     W = h.W
     start = torch.from_numpy(np.ascontiguousarray(h.start_states[w.request_template]).view(np.int32).copy()).cuda()
 
-    # ---- untimed pre-pass: produce the token trajectory on the GPU (sampler stand-in) ----
+    # ---- untimed pre-pass: produce the token trajectory on the GPU (sampler stand-in), keep the
+    # states at the first warm-up step and the masks of the timed steps ----
     draws = torch.from_numpy(w.token_draws(total).view(np.int64)).cuda()
     tokens = torch.empty((total, B), dtype=torch.int32, device="cuda")
     states = start.clone()
     mask = torch.empty((B, W), dtype=torch.int32, device="cuda")
-    popcount8 = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device="cuda")
-    n_allowed = torch.zeros((), dtype=torch.int64, device="cuda")
+    masks_timed = torch.empty((K, B, W), dtype=torch.int32, device="cuda")
+    window_states = None
     for k in range(total):
+        if k == k0 - Wm:
+            window_states = states.clone()
         h.fill_masks(states, mask)
-        if k >= Wm:                                   # allowed tokens in the timed steps' masks
-            n_allowed += popcount8[mask.view(torch.uint8).long()].sum()
+        if k >= k0:
+            masks_timed[k - k0].copy_(mask)
         wg.select_tokens(mask, V, draws[k], tokens[k])
         h.advance(states, tokens[k])
     torch.cuda.synchronize()
     assert h.error_count() == 0, "trajectory generation fed an illegal token"
     pre = h.cache_stats()
-    disallowed_per_step = B * V - n_allowed.item() / float(K)
+    popcount8 = torch.tensor([bin(i).count("1") for i in range(256)], dtype=torch.int64, device="cuda")
+    n_allowed = sum(int(popcount8[masks_timed[k].view(torch.uint8).long()].sum().item()) for k in range(K))
+    disallowed_per_step = B * V - n_allowed / float(K)
 
-    # a plain device copy of known size (512 MiB in, 512 MiB out, larger than every cache): the reference against which
-    # the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the other kernels are scaled
+    # a plain device copy of known size (512 MiB in, 512 MiB out, larger than every cache): the
+    # reference against which the rocprofv3 FETCH_SIZE / WRITE_SIZE counters of the other kernels are
+    # scaled, and the measured ceiling of a streaming kernel on this GPU
     calib_src = torch.randint(0, 255, (512 << 20,), dtype=torch.uint8, device="cuda")
     calib_dst = torch.empty_like(calib_src)
-    torch.cuda.synchronize()
-    calib_dst.copy_(calib_src)
-    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    copy_ms = []
+    for _ in range(6):
+        torch.cuda.synchronize()
+        e0.record()
+        calib_dst.copy_(calib_src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_ms.append(e0.elapsed_time(e1))
+    copy_ceiling_gbs = 2.0 * (512 << 20) / (min(copy_ms[1:]) * 1e-3) / 1e9
     del calib_src, calib_dst
 
     # logits ring (values are irrelevant to the work done; N(0, sigma) as the workload says)
     ring = [(torch.randn((B, V), device="cuda", dtype=torch.float32) * w.sigma).to(tdt) for _ in range(4)]
-
-    def run(cold, lo, hi):
-        for k in range(lo, hi):
-            if cold:
-                h.cache_clear()
-            h.fill_masks(states, mask)
-            wg.apply_mask(ring[k & 3], mask)
-            h.advance(states, tokens[k])
-
-    def timed(cold):
-        states.copy_(start)
-        if cold:
-            h.cache_clear()
-        run(cold, 0, Wm)
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        run(cold, Wm, total)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) / K
 
     def step(cold, k):
         if cold:
@@ -266,34 +281,101 @@ def main():
         wg.apply_mask(ring[k & 3], mask)
         h.advance(states, tokens[k])
 
-    # ---- per-kernel durations over the same timed region, HIP events on the launch stream ----
-    def kernel_times(cold):
-        states.copy_(start)
+    def rewind(cold):
+        """Back to the first warm-up step, then the warm-up steps."""
+        states.copy_(window_states)
         if cold:
             h.cache_clear()
-        run(cold, 0, Wm)
+        for k in range(k0 - Wm, k0):
+            step(cold, k)
+
+    def ramp(prepare, one_step):
+        """Keeps the GPU busy with the loop that is about to be timed until its clocks have settled."""
+        t_end = time.perf_counter() + RAMP_SECONDS
+        while time.perf_counter() < t_end:
+            prepare()
+            for k in range(k0, total):
+                one_step(k)
+            torch.cuda.synchronize()
+
+    def passes(prepare, one_step, n=N_PASSES):
+        """n timed passes over the K steps of the window: seconds per step of each pass."""
+        ramp(prepare, one_step)
+        out = []
+        for _ in range(n):
+            prepare()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for k in range(k0, total):
+                one_step(k)
+            torch.cuda.synchronize()
+            out.append((time.perf_counter() - t) / K)
+        return out
+
+    def timed(cold):
+        return passes(lambda: rewind(cold), lambda k: step(cold, k))
+
+    # ---- per-kernel durations over the same timed steps, HIP events on the launch stream ----
+    def kernel_times(cold):
+        ramp(lambda: rewind(cold), lambda k: step(cold, k))
+        rewind(cold)
         torch.cuda.synchronize()
         h.profile_enable(True)
         h.profile_read()
-        for k in range(Wm, total):
-            step(cold, k)
+        for k in range(k0, total):
+            if cold:
+                h.cache_clear()
+            h.fill_masks(states, mask)
+            h.profile_apply_mask(ring[k & 3], mask)
+            h.advance(states, tokens[k])
         torch.cuda.synchronize()
         p = h.profile_read()
         h.profile_enable(False)
-        return {k[:-3] + "_us": 1e3 * p[k] / K for k in ("lookup_ms", "scan_ms", "build_ms", "gather_ms", "advance_ms")}
+        return {k[:-3] + "_us": 1e3 * p[k] / K
+                for k in ("lookup_ms", "scan_ms", "build_ms", "gather_ms", "advance_ms", "apply_ms")}
+
+    # ---- the whole step in one call: advance + fill + apply ----
+    def single_step(cold, k):
+        if cold:
+            h.cache_clear()
+        h.decode_step(states, tokens[k - 1], mask, ring[k & 3])
+
+    def single_rewind(cold):
+        # (the token before the first warm-up step is not part of the window: that step only fills)
+        states.copy_(window_states)
+        if cold:
+            h.cache_clear()
+        h.decode_step(states, None, mask, ring[0])
+        for k in range(k0 - Wm + 1, k0):
+            single_step(cold, k)
+
+    def timed_single(cold):
+        return passes(lambda: single_rewind(cold), lambda k: single_step(cold, k))
+
+    def decode_kernel_times(cold):
+        """Per-kernel durations of wg_decode_step: its first kernel counts as lookup, its last as gather."""
+        ramp(lambda: single_rewind(cold), lambda k: single_step(cold, k))
+        single_rewind(cold)
+        torch.cuda.synchronize()
+        h.profile_enable(True)
+        h.profile_read()
+        for k in range(k0, total):
+            single_step(cold, k)
+        torch.cuda.synchronize()
+        p = h.profile_read()
+        h.profile_enable(False)
+        return {"advance_lookup_us": 1e3 * p["lookup_ms"] / K, "scan_us": 1e3 * p["scan_ms"] / K,
+                "build_us": 1e3 * p["build_ms"] / K, "gather_apply_us": 1e3 * p["gather_ms"] / K}
 
     # ---- spread of the step time: one event per step boundary (their cost is inside the figures) ----
     def step_spread(cold):
-        states.copy_(start)
-        if cold:
-            h.cache_clear()
-        run(cold, 0, Wm)
+        rewind(cold)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
         torch.cuda.synchronize()
         ev[0].record()
-        for k in range(Wm, total):
+        for k in range(k0, total):
             step(cold, k)
-            ev[k - Wm + 1].record()
+            ev[k - k0 + 1].record()
         torch.cuda.synchronize()
         us = np.array([1e3 * ev[i].elapsed_time(ev[i + 1]) for i in range(K)])
         return {"median_us": float(np.median(us)), "p10_us": float(np.percentile(us, 10)),
@@ -301,14 +383,11 @@ def main():
 
     # ---- spread of the calls of a step: an event after each call (their cost is inside the figures) ----
     def parts_spread(cold):
-        states.copy_(start)
-        if cold:
-            h.cache_clear()
-        run(cold, 0, Wm)
+        rewind(cold)
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(K)]
         torch.cuda.synchronize()
-        for k in range(Wm, total):
-            e = ev[k - Wm]
+        for k in range(k0, total):
+            e = ev[k - k0]
             if cold:
                 h.cache_clear()
             e[0].record()
@@ -328,182 +407,218 @@ def main():
 
     # ---- the decode loop with advance and the next fill in one call ----
     def timed_fused(cold):
-        def go(lo, hi):
-            for k in range(lo, hi):
-                wg.apply_mask(ring[k & 3], mask)
-                if cold:
-                    h.cache_clear()
-                h.advance_fill_masks(states, tokens[k], mask)
-        states.copy_(start)
-        if cold:
-            h.cache_clear()
-        h.fill_masks(states, mask)
-        go(0, Wm)
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        go(Wm, total)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) / K
+        def one(k):
+            wg.apply_mask(ring[k & 3], mask)
+            if cold:
+                h.cache_clear()
+            h.advance_fill_masks(states, tokens[k], mask)
 
-    # ---- the whole step in one call: advance + fill + apply ----
-    def timed_single(cold):
-        def go(lo, hi):
-            for k in range(lo, hi):
-                if cold:
-                    h.cache_clear()
-                h.decode_step(states, tokens[k - 1] if k else None, mask, ring[k & 3])
-        states.copy_(start)
-        if cold:
-            h.cache_clear()
-        go(0, Wm)
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        go(Wm, total)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) / K
+        def prepare():
+            states.copy_(window_states)
+            if cold:
+                h.cache_clear()
+            h.fill_masks(states, mask)
+            for k in range(k0 - Wm, k0):
+                one(k)
+        return passes(prepare, one)
 
-    # Warm first: every key was cached by the pre-pass.  The warm step is short enough for host
-    # launch jitter to show, so it is the best of three timed passes (the cold headline below is
-    # a single pass).
-    sec_warm = min(timed(False) for _ in range(3))
+    med = lambda xs: float(np.median(xs))
+
+    # Warm first: every key of the window was cached by the pre-pass.
+    s_w0 = h.cache_stats()
+    warm_passes = timed(False)
+    s_w1 = h.cache_stats()
+    sec_warm = med(warm_passes)
+    hit_rate = (s_w1["hits"] - s_w0["hits"]) / float(max(1, s_w1["lookups"] - s_w0["lookups"]))
+    assert s_w1["builds"] == pre["builds"], "a warm pass built a mask"
     kt_warm = kernel_times(False)
-    spread_warm = step_spread(False)
-    parts_warm = parts_spread(False)
-    assert h.cache_stats()["builds"] == pre["builds"], "a warm pass built a mask"
-    # (the fused loop also fills for the state after the last step, which no pass before it saw)
-    sec_fused_warm = min(timed_fused(False) for _ in range(3))
-    sec_single_warm = min(timed_single(False) for _ in range(3))
+    single_warm_passes = timed_single(False)
+    sec_single_warm = med(single_warm_passes)
+    dk_warm = decode_kernel_times(False)
 
-    # ---- the same K warm steps recorded once into a HIP graph and replayed (no host work per launch) ----
-    def timed_graph_warm():
-        side = torch.cuda.Stream()
-        states.copy_(start)
-        torch.cuda.synchronize()
-        with torch.cuda.stream(side):
-            for k in range(Wm):
-                h.decode_step(states, tokens[k - 1] if k else None, mask, ring[k & 3], stream=side)
-        side.synchronize()
-        after_warmup = states.clone()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=side):
-            for k in range(Wm, total):
-                h.decode_step(states, tokens[k - 1], mask, ring[k & 3], stream=side)
-        best = None
-        for _ in range(3):
-            states.copy_(after_warmup)
-            torch.cuda.synchronize()
-            t = time.perf_counter()
-            graph.replay()
-            torch.cuda.synchronize()
-            dt = (time.perf_counter() - t) / K
-            best = dt if best is None else min(best, dt)
-        return best
-
-    sec_graph_warm = timed_graph_warm()
     s0 = h.cache_stats()
-    sec_cold = timed(True)
+    cold_passes = timed(True)
     s1 = h.cache_stats()
-    builds_per_step = (s1["builds"] - s0["builds"]) / float(total)
-    scans_per_step = (s1["class_scans"] - s0["class_scans"]) / float(total)
-    entries_per_step = (s1["entries_walked"] - s0["entries_walked"]) / float(total)
+    sec_cold = med(cold_passes)
+    # (per step of the timed loop: the ramp, the warm-up and the timed steps all clear before every fill)
+    n_cold_steps = float(s1["lookups"] - s0["lookups"]) / B
+    builds_per_step = (s1["builds"] - s0["builds"]) / n_cold_steps
+    scans_per_step = (s1["class_scans"] - s0["class_scans"]) / n_cold_steps
+    entries_per_step = (s1["entries_walked"] - s0["entries_walked"]) / n_cold_steps
     kt_cold = kernel_times(True)
-    spread_cold = step_spread(True)
-    parts_cold = parts_spread(True)
-    sec_fused_cold = timed_fused(True)
-    sec_single_cold = timed_single(True)
-    # apply is a single kernel outside the handle: time a back-to-back run of it
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    e0.record()
-    for k in range(K):
-        wg.apply_mask(ring[k & 3], mask)
-    e1.record()
-    torch.cuda.synchronize()
-    apply_us = 1e3 * e0.elapsed_time(e1) / K
-    kt_cold["apply_us"] = kt_warm["apply_us"] = apply_us
-    # The mask that loop applied, by groups of 32 tokens (one mask word; 64 bytes of bf16 logits):
+    single_cold_passes = timed_single(True)
+    sec_single_cold = med(single_cold_passes)
+    dk_cold = decode_kernel_times(True)
+
+    apply_us = kt_cold["apply_us"]
+    # The masks of the timed steps, by groups of 32 tokens (one mask word; 64 bytes of bf16 logits):
     # a group that is disallowed as a whole is written as full blocks; a store into a mixed one
     # covers part of a block, which costs more than writing the block whole (--apply-patterns).
-    n_words = float(B * W)
-    words_full = (mask == 0).sum().item() / n_words
-    words_untouched = (mask == -1).sum().item() / n_words
+    n_words = float(K * B * W)
+    words_full = (masks_timed == 0).sum().item() / n_words
+    words_untouched = (masks_timed == -1).sum().item() / n_words
     words_mixed = 1.0 - words_full - words_untouched
 
-    # ---- greedy variant of the step: fill, masked argmax (logits only read), advance ----
-    greedy_tok = torch.empty(B, dtype=torch.int32, device="cuda")
+    def recache():
+        """After cold passes: one untimed pass without clears, so that the window's keys are all cached again."""
+        rewind(False)
+        for k in range(k0, total):
+            step(False, k)
+        torch.cuda.synchronize()
 
-    def run_greedy(cold, lo, hi):
-        for k in range(lo, hi):
+    extra = {}
+    if not args.brief:
+        spread_cold, parts_cold = step_spread(True), parts_spread(True)
+        recache()
+        spread_warm, parts_warm = step_spread(False), parts_spread(False)
+        sec_fused_warm, sec_fused_cold = med(timed_fused(False)), med(timed_fused(True))
+
+        # ---- the same K warm steps recorded once into a HIP graph and replayed (no host work per launch) ----
+        def timed_graph_warm():
+            side = torch.cuda.Stream()
+            states.copy_(window_states)
+            torch.cuda.synchronize()
+            with torch.cuda.stream(side):
+                h.decode_step(states, None, mask, ring[0], stream=side)
+                for k in range(k0 - Wm + 1, k0):
+                    h.decode_step(states, tokens[k - 1], mask, ring[k & 3], stream=side)
+            side.synchronize()
+            after_warmup = states.clone()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                for k in range(k0, total):
+                    h.decode_step(states, tokens[k - 1], mask, ring[k & 3], stream=side)
+            out = []
+            for _ in range(N_PASSES):
+                states.copy_(after_warmup)
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                graph.replay()
+                torch.cuda.synchronize()
+                out.append((time.perf_counter() - t) / K)
+            return med(out)
+
+        recache()
+        sec_graph_warm = timed_graph_warm()
+
+        # ---- greedy variant of the step: fill, masked argmax (logits only read), advance ----
+        greedy_tok = torch.empty(B, dtype=torch.int32, device="cuda")
+        fresh = [(torch.randn((B, V), device="cuda", dtype=torch.float32) * w.sigma).to(tdt) for _ in range(4)]
+
+        def greedy_step(cold, k):
             if cold:
                 h.cache_clear()
             h.fill_masks(states, mask)
             wg.masked_argmax(fresh[k & 3], mask, greedy_tok)
             h.advance(states, greedy_tok)
 
-    def timed_greedy(cold):
-        if not cold:                                  # a first pass over the same trajectory caches its keys
-            states.copy_(start)
-            h.cache_clear()
-            run_greedy(False, 0, total)
-        states.copy_(start)
-        if cold:
-            h.cache_clear()
-        run_greedy(cold, 0, Wm)
-        torch.cuda.synchronize()
-        t = time.perf_counter()
-        run_greedy(cold, Wm, total)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - t) / K
+        def timed_greedy(cold):
+            def prepare():
+                states.copy_(start)
+                if cold:
+                    h.cache_clear()
+                for k in range(Wm):
+                    greedy_step(cold, k)
+            if not cold:                                  # a first pass over the same trajectory caches its keys
+                h.cache_clear()
+                prepare()
+                for k in range(k0, total):
+                    greedy_step(False, k)
+            return med(passes(prepare, lambda k: greedy_step(cold, k), n=3))
 
-    fresh = [(torch.randn((B, V), device="cuda", dtype=torch.float32) * w.sigma).to(tdt) for _ in range(4)]
-    sec_greedy_cold = timed_greedy(True)
-    sec_greedy_warm = timed_greedy(False)
-    assert h.error_count() == 0, "greedy decoding chose an illegal token"
-    torch.cuda.synchronize()
-    e0.record()
-    for k in range(K):
-        wg.masked_argmax(fresh[k & 3], mask, greedy_tok)
-    e1.record()
-    torch.cuda.synchronize()
-    argmax_us = 1e3 * e0.elapsed_time(e1) / K
-    # the candidates of top-k sampling under the same masks (logits only read)
-    topk_k = 50
-    topk_ids = torch.empty((B, topk_k), dtype=torch.int32, device="cuda")
-    topk_vals = torch.empty((B, topk_k), dtype=tdt, device="cuda")
-    topk_work = torch.empty(wg.masked_topk_workspace(B, V, topk_k), dtype=torch.uint8, device="cuda")
-    for k in range(4):
-        wg.masked_topk(fresh[k & 3], mask, topk_ids, topk_vals, topk_work)
-    torch.cuda.synchronize()
-    e0.record()
-    for k in range(K):
-        wg.masked_topk(fresh[k & 3], mask, topk_ids, topk_vals, topk_work)
-    e1.record()
-    torch.cuda.synchronize()
-    topk_us = 1e3 * e0.elapsed_time(e1) / K
+        sec_greedy_cold = timed_greedy(True)
+        sec_greedy_warm = timed_greedy(False)
+        assert h.error_count() == 0, "greedy decoding chose an illegal token"
+        torch.cuda.synchronize()
+        e0.record()
+        for k in range(K):
+            wg.masked_argmax(fresh[k & 3], masks_timed[k], greedy_tok)
+        e1.record()
+        torch.cuda.synchronize()
+        argmax_us = 1e3 * e0.elapsed_time(e1) / K
+        # the candidates of top-k sampling under the same masks (logits only read)
+        topk_k = 50
+        topk_ids = torch.empty((B, topk_k), dtype=torch.int32, device="cuda")
+        topk_vals = torch.empty((B, topk_k), dtype=tdt, device="cuda")
+        topk_work = torch.empty(wg.masked_topk_workspace(B, V, topk_k), dtype=torch.uint8, device="cuda")
+        for k in range(4):
+            wg.masked_topk(fresh[k & 3], masks_timed[k % K], topk_ids, topk_vals, topk_work)
+        torch.cuda.synchronize()
+        e0.record()
+        for k in range(K):
+            wg.masked_topk(fresh[k & 3], masks_timed[k], topk_ids, topk_vals, topk_work)
+        e1.record()
+        torch.cuda.synchronize()
+        topk_us = 1e3 * e0.elapsed_time(e1) / K
+        row_b = V / 8.0
+        extra = {
+            "step_spread": {"note": "per-step times between events recorded at the step boundaries "
+                                    "(fill + apply + advance, event cost included)",
+                            "cold": spread_cold, "warm": spread_warm},
+            "calls_spread": {"note": "the calls of a step between events recorded after each (event cost and the host's "
+                                     "launch gaps included, so the parts add up to more than the step)",
+                             "cold": parts_cold, "warm": parts_warm},
+            "fused_advance_fill": {"note": "the same steps through wg_apply_mask + wg_advance_fill_masks",
+                                   "cold_ms_per_step": sec_fused_cold * 1e3, "warm_ms_per_step": sec_fused_warm * 1e3,
+                                   "cold_request_steps_per_s": B / sec_fused_cold,
+                                   "warm_request_steps_per_s": B / sec_fused_warm},
+            "greedy": {"note": "fill + wg_masked_argmax + advance; logits are read, never written",
+                       "cold_ms_per_step": sec_greedy_cold * 1e3, "warm_ms_per_step": sec_greedy_warm * 1e3,
+                       "cold_request_steps_per_s": B / sec_greedy_cold, "warm_request_steps_per_s": B / sec_greedy_warm,
+                       "masked_argmax_us": argmax_us,
+                       "masked_argmax_dense_read_GBs": B * (row_b + esz * V) / (argmax_us * 1e-6) / 1e9},
+            "topk": {"note": "wg_masked_topk on the masks of the timed steps, k = %d; logits are read, never written" % topk_k,
+                     "k": topk_k, "masked_topk_us": topk_us,
+                     "masked_topk_dense_read_GBs": B * (row_b + esz * V) / (topk_us * 1e-6) / 1e9},
+            "host_setup": {"vocabulary_indexes_ms": vocab_ms, "compile_all_instances_ms": compile_ms,
+                           "instances": len(w.texts),
+                           "add_one_instance_us_median": float(np.median(join_us)) if join_us else None,
+                           "add_one_instance_us_p90": float(np.percentile(join_us, 90)) if join_us else None,
+                           "add_one_instance_call_only_us_median": float(np.median(join_call_us)) if join_call_us else None,
+                           "add_one_instance_call_only_us_p90": float(np.percentile(join_call_us, 90)) if join_call_us else None},
+            "hip_graph": {"note": "the K warm steps through wg_decode_step recorded once into a HIP graph and replayed",
+                          "warm_ms_per_step": sec_graph_warm * 1e3},
+        }
 
-    # ---- algorithmic bytes per launch of each kernel ----
+    # ---- algorithmic bytes per launch of each kernel: what the method has to move, not the
+    # dense work it avoids ----
     sum_len = int(w.vocab.offsets[-1])
     row_bytes = V / 8.0
-    scan_bytes_per_class = sum_len + V + 2 * row_bytes        # token bytes + length byte + two rows
-    key_bytes_per_key = 3 * row_bytes                           # two class rows in, one row out
+    n_class_rows = 3.0                                        # stay, end and their union
+    scan_bytes_per_class = sum_len + V + n_class_rows * row_bytes      # token bytes + a length byte per token + the rows written
+    key_bytes_per_key = 3 * row_bytes                           # one class row in, the row out twice (cache and bitmask)
     entry_bytes = 8.0
-    gather_bytes = B * 2 * row_bytes
+    gather_rows = B - builds_per_step                           # rows the gather copies (a claimer's row is written by key_build)
+    gather_bytes_cold = gather_rows * 2 * row_bytes
+    gather_bytes_warm = B * 2 * row_bytes
     apply_dense_bytes = B * (row_bytes + 2 * esz * V)
     apply_min_bytes = B * row_bytes + esz * disallowed_per_step      # mask in, -inf out, nothing else
-    per_kernel = {
+    state_bytes = B * (8 + 4 + 8)                               # state in and out, token in
+    alg = {
+        "lookup": (B * 16.0, kt_cold["lookup_us"]),
         "class_scan": (scans_per_step * scan_bytes_per_class, kt_cold["scan_us"]),
         "key_build": (builds_per_step * key_bytes_per_key + entries_per_step * entry_bytes, kt_cold["build_us"]),
-        "gather": (gather_bytes, kt_cold["gather_us"]),
-        "apply": (apply_min_bytes, apply_us),
+        "gather": (gather_bytes_cold, kt_cold["gather_us"]),
+        "apply": (apply_min_bytes, kt_cold["apply_us"]),
+        "advance": (state_bytes + B * (sum_len / float(V)), kt_cold["advance_us"]),
     }
-    dominant = max(per_kernel, key=lambda k: per_kernel[k][1])
-    dom_bytes, dom_us = per_kernel[dominant]
-    dom_gbs = dom_bytes / (dom_us * 1e-6) / 1e9 if dom_us > 0 else 0.0
-    # whole-step accounting in the terms the throughput target is stated in: one streamed pass
-    # over the vocabulary per built key, the gather, and the dense read-modify-write of apply
+    traffic_ok = kernel_source_sha256() == TRAFFIC_SOURCE_SHA256
+    kernels = []
+    for name, (nbytes, us) in alg.items():
+        gbs = nbytes / (us * 1e-6) / 1e9 if us > 0 else 0.0
+        kernels.append({"kernel": name, "algorithmic_bytes_per_launch": nbytes, "us_per_launch": us,
+                        "achieved_GBs": gbs, "frac": gbs / HBM_PEAK_GBS,
+                        "traffic": TRAFFIC_BYTES.get(name) if traffic_ok else None,
+                        "bound": "hbm" if name in ("class_scan", "key_build", "gather", "apply") else "latency"})
+    dominant = max((k for k in kernels if k["bound"] == "hbm"), key=lambda k: k["us_per_launch"])
+    method_bytes_cold = sum(v[0] for v in alg.values())
+    method_bytes_warm = alg["lookup"][0] + gather_bytes_warm + apply_min_bytes + alg["advance"][0]
+    # the same step in the accounting the throughput target is stated in: one streamed pass over the
+    # vocabulary per built key, the gather, and a dense read-modify-write of the logits.  The kernels
+    # move none of these bytes; the figure says what a scan-per-key design would have to sustain.
     scan_per_key_bytes = sum_len + V + row_bytes
-    cold_bytes = builds_per_step * scan_per_key_bytes + gather_bytes + apply_dense_bytes
-    warm_bytes = gather_bytes + apply_dense_bytes
+    dense_cold = builds_per_step * scan_per_key_bytes + B * 2 * row_bytes + apply_dense_bytes
+    dense_warm = B * 2 * row_bytes + apply_dense_bytes
 
     out = {
         "metric": "masked request-steps/sec at V=151,936 (cold cache)",
@@ -516,56 +631,46 @@ def main():
         "config": {"workload": "config %d (%s): B=%d, V=%d, %s logits, %d template instances, "
                                "seeded token stream" % (w.index, w.name, B, V, w.dtype, len(w.texts)),
                    "cache": "cold = cleared before every step; warm = all keys cached",
+                   "window": "timed steps are steps %d .. %d of the trajectory" % (k0, total - 1),
+                   "timing": "median of %d passes over the K steps, after %.0f ms of the same loop" % (N_PASSES, RAMP_SECONDS * 1e3),
                    "logits_dtype": w.dtype},
-        "warm": {"value": B / sec_warm, "unit": "request-steps/s", "ms_per_step": sec_warm * 1e3,
-                 "hit_rate": 1.0, "step_GBs": warm_bytes / sec_warm / 1e9,
-                 "frac_of_hbm_peak": warm_bytes / sec_warm / 1e9 / HBM_PEAK_GBS},
-        "cold": {"keys_built_per_step": builds_per_step, "class_scans_per_step": scans_per_step,
+        "roofline": {"kernel": dominant["kernel"], "bound": "hbm", "achieved": dominant["achieved_GBs"],
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": dominant["frac"],
+                     "traffic": dominant["traffic"],
+                     "algorithmic_bytes_per_launch": dominant["algorithmic_bytes_per_launch"],
+                     "us_per_launch": dominant["us_per_launch"],
+                     "kernels": kernels,
+                     "copy_ceiling_GBs": copy_ceiling_gbs},
+        "cold": {"ms_per_step_passes": [s * 1e3 for s in cold_passes],
+                 "keys_built_per_step": builds_per_step, "class_scans_per_step": scans_per_step,
                  "exit_entries_per_step": entries_per_step,
-                 "step_GBs_scan_per_key_accounting": cold_bytes / sec_cold / 1e9,
-                 "frac_of_hbm_peak": cold_bytes / sec_cold / 1e9 / HBM_PEAK_GBS},
-        "roofline": {"kernel": dominant, "bound": "hbm", "achieved": dom_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": dom_gbs / HBM_PEAK_GBS,
-                     "traffic": TRAFFIC_BYTES[dominant] if kernel_source_sha256() == TRAFFIC_SOURCE_SHA256 else None,
-                     "algorithmic_bytes_per_launch": dom_bytes, "us_per_launch": dom_us},
+                 "method_bytes_per_step": method_bytes_cold,
+                 "step_frac_method_bytes": method_bytes_cold / sec_cold / 1e9 / HBM_PEAK_GBS,
+                 "dense_equivalent_GBs": dense_cold / sec_cold / 1e9,
+                 "frac_of_hbm_peak_dense_equivalent": dense_cold / sec_cold / 1e9 / HBM_PEAK_GBS},
+        "warm": {"value": B / sec_warm, "unit": "request-steps/s", "ms_per_step": sec_warm * 1e3,
+                 "ms_per_step_passes": [s * 1e3 for s in warm_passes],
+                 "hit_rate": hit_rate,
+                 "method_bytes_per_step": method_bytes_warm,
+                 "step_frac_method_bytes": method_bytes_warm / sec_warm / 1e9 / HBM_PEAK_GBS,
+                 "dense_equivalent_GBs": dense_warm / sec_warm / 1e9,
+                 "frac_of_hbm_peak_dense_equivalent": dense_warm / sec_warm / 1e9 / HBM_PEAK_GBS},
         "kernels_us_per_step": {"cold": kt_cold, "warm": kt_warm},
-        "step_spread": {"note": "per-step times between events recorded at the step boundaries "
-                                "(fill + apply + advance, event cost included)",
-                        "cold": spread_cold, "warm": spread_warm},
-        "calls_spread": {"note": "the calls of a step between events recorded after each (event cost and the host's "
-                                 "launch gaps included, so the parts add up to more than the step)",
-                         "cold": parts_cold, "warm": parts_warm},
         "single_call_step": {"note": "the same steps through wg_decode_step (advance + fill + apply, four launches)",
                              "cold_ms_per_step": sec_single_cold * 1e3, "warm_ms_per_step": sec_single_warm * 1e3,
                              "cold_request_steps_per_s": B / sec_single_cold,
                              "warm_request_steps_per_s": B / sec_single_warm,
-                             "warm_ms_per_step_hip_graph": sec_graph_warm * 1e3},
-        "fused_advance_fill": {"note": "the same steps through wg_apply_mask + wg_advance_fill_masks",
-                               "cold_ms_per_step": sec_fused_cold * 1e3, "warm_ms_per_step": sec_fused_warm * 1e3,
-                               "cold_request_steps_per_s": B / sec_fused_cold,
-                               "warm_request_steps_per_s": B / sec_fused_warm},
-        "kernels_GBs": {k: (v[0] / (v[1] * 1e-6) / 1e9 if v[1] > 0 else None) for k, v in per_kernel.items()},
+                             "kernels_us_per_step": {"cold": dk_cold, "warm": dk_warm}},
         "apply": {"disallowed_fraction": disallowed_per_step / float(B * V),
                   "min_bytes_GBs": apply_min_bytes / (apply_us * 1e-6) / 1e9,
                   "dense_equivalent_GBs": apply_dense_bytes / (apply_us * 1e-6) / 1e9,
                   "groups_of_32_tokens": {"untouched": words_untouched, "fully_disallowed": words_full, "mixed": words_mixed}},
-        "greedy": {"note": "fill + wg_masked_argmax + advance; logits are read, never written",
-                   "cold_ms_per_step": sec_greedy_cold * 1e3, "warm_ms_per_step": sec_greedy_warm * 1e3,
-                   "cold_request_steps_per_s": B / sec_greedy_cold, "warm_request_steps_per_s": B / sec_greedy_warm,
-                   "masked_argmax_us": argmax_us,
-                   "masked_argmax_dense_read_GBs": B * (row_bytes + esz * V) / (argmax_us * 1e-6) / 1e9},
-        "topk": {"note": "wg_masked_topk on the masks of the last step, k = %d; logits are read, never written" % topk_k,
-                 "k": topk_k, "masked_topk_us": topk_us,
-                 "masked_topk_dense_read_GBs": B * (row_bytes + esz * V) / (topk_us * 1e-6) / 1e9},
-        "host_setup": {"vocabulary_indexes_ms": vocab_ms, "compile_all_instances_ms": compile_ms,
-                       "instances": len(w.texts),
-                       "add_one_instance_us_median": float(np.median(join_us)) if join_us else None,
-                       "add_one_instance_us_p90": float(np.percentile(join_us, 90)) if join_us else None,
-                       "add_one_instance_call_only_us_median": float(np.median(join_call_us)) if join_call_us else None,
-                       "add_one_instance_call_only_us_p90": float(np.percentile(join_call_us, 90)) if join_call_us else None},
         "prepass": {"builds": pre["builds"], "lookups": pre["lookups"], "class_scans": pre["class_scans"]},
+        "cpu_model": cpu_model(),
     }
+    out.update(extra)
     if cpu is not None:
+        cpu["cpu_model"] = cpu_model()
         out["cpu_baseline"] = cpu
     print(json.dumps(out))
 

@@ -316,9 +316,15 @@ const char *wg_last_error(void);
 typedef struct {
     uint64_t fill_calls, advance_calls;
     double lookup_ms, scan_ms, build_ms, gather_ms, advance_ms;   /* summed kernel durations */
+    uint64_t apply_calls;
+    double apply_ms;
 } wg_profile_t;
 int wg_profile_enable(wg_handle_t h, int on);
 int wg_profile_read(wg_handle_t h, wg_profile_t *host_out);
+/* wg_apply_mask with its kernel's begin and end taken into the handle's record while timing is
+ * enabled (apply_calls, apply_ms); exactly wg_apply_mask while it is not. */
+int wg_profile_apply_mask(wg_handle_t h, void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V,
+                          int64_t row_stride_elems, const uint32_t *d_bitmask, void *stream);
 
 /* ---- sampler stand-in for harnesses (not part of the decoding path) ----------------------
  * d_tokens[b] <- index of the (d_draws[b] mod popcount)-th set bit of mask row b, or -1 for

@@ -46,7 +46,7 @@ class _StateInfo(C.Structure):
 class _Profile(C.Structure):
     _fields_ = [("fill_calls", C.c_uint64), ("advance_calls", C.c_uint64), ("lookup_ms", C.c_double),
                 ("scan_ms", C.c_double), ("build_ms", C.c_double), ("gather_ms", C.c_double),
-                ("advance_ms", C.c_double)]
+                ("advance_ms", C.c_double), ("apply_calls", C.c_uint64), ("apply_ms", C.c_double)]
 
 
 EXPORTS = [
@@ -58,7 +58,7 @@ EXPORTS = [
     "wg_add_instances", "wg_num_instances", "wg_cache_resize", "wg_table_add_instances",
     "wg_table_num_instances", "wg_advance_fill_masks", "wg_regex_to_template",
     "wg_decode_step", "wg_masked_topk", "wg_masked_topk_workspace", "wg_reserve_batch", "wg_max_batch",
-    "wg_masked_topk_static", "wg_masked_topk_static_capacity",
+    "wg_masked_topk_static", "wg_masked_topk_static_capacity", "wg_profile_apply_mask",
 ]
 
 
@@ -126,6 +126,7 @@ def load_library():
     L.wg_select_tokens.argtypes = [vp, u32, u32, vp, vp, vp]
     L.wg_profile_enable.argtypes = [vp, C.c_int]
     L.wg_profile_read.argtypes = [vp, C.POINTER(_Profile)]
+    L.wg_profile_apply_mask.argtypes = [vp, vp, C.c_int, u32, u32, i64, vp, vp]
     _lib = L
     return L
 
@@ -352,6 +353,18 @@ class Handle:
         p = _Profile()
         _check(load_library().wg_profile_read(self._h, C.byref(p)))
         return {k: getattr(p, k) for k, _ in _Profile._fields_}
+
+    def profile_apply_mask(self, logits, bitmask, stream=None):
+        """wg_profile_apply_mask: wg_apply_mask, timed into this handle's record while timing is enabled."""
+        import torch
+        dt = {torch.float32: F32, torch.bfloat16: BF16}.get(logits.dtype)
+        if dt is None or logits.dim() != 2 or not logits.is_cuda or logits.stride(1) != 1:
+            raise ValueError("logits must be a [B, V] float32 or bfloat16 device tensor with unit inner stride")
+        B, V = logits.shape
+        if tuple(bitmask.shape) != (B, (V + 31) // 32):
+            raise ValueError("bitmask must be [B, ceil(V/32)]")
+        _check(load_library().wg_profile_apply_mask(self._h, C.c_void_p(logits.data_ptr()), dt, B, V, logits.stride(0),
+                                                    _dev(bitmask, torch.int32, "bitmask"), _stream_ptr(stream)))
 
     def error_count(self):
         n = C.c_uint64()

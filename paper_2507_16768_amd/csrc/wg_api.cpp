@@ -59,6 +59,7 @@ struct wg_handle_s {
     bool profiling = false;
     std::vector<hipEvent_t> fill_events;       // 8 per wg_fill_masks call: begin / end of each kernel
     std::vector<hipEvent_t> advance_events;    // 2 per wg_advance call
+    std::vector<hipEvent_t> apply_events;      // 2 per wg_profile_apply_mask call
     std::vector<hipEvent_t> spare_events;
     wg_handle_s(uint32_t flags, uint32_t lmax) : low(flags, lmax) {}
 };
@@ -439,7 +440,7 @@ void wg_destroy(wg_handle_t h) {
     (void)hipFree(h->dc.class_built); (void)hipFree(h->dc.class_rows);
     (void)hipFree(h->d_class_entries); (void)hipFree(h->dc.class_count);
     for (ExitEntry *b : h->class_slabs) (void)hipFree(b);
-    for (auto *v : {&h->fill_events, &h->advance_events, &h->spare_events})
+    for (auto *v : {&h->fill_events, &h->advance_events, &h->apply_events, &h->spare_events})
         for (hipEvent_t e : *v) if (e) (void)hipEventDestroy(e);
     delete h;
 }
@@ -600,7 +601,21 @@ int wg_apply_mask(void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V, int6
     if (dtype != WG_F32 && dtype != WG_BF16) return fail(WG_ERR_INVALID, "wg_apply_mask: unknown dtype");
     if (row_stride_elems < (int64_t)V) return fail(WG_ERR_INVALID, "wg_apply_mask: row stride smaller than V");
     if (B > kMaxBatch) return fail(WG_ERR_INVALID, "wg_apply_mask: B above 65535");
-    WG_HIP(launch_apply(d_logits, dtype, B, V, row_stride_elems, d_bitmask, static_cast<hipStream_t>(stream)));
+    WG_HIP(launch_apply(d_logits, dtype, B, V, row_stride_elems, d_bitmask, static_cast<hipStream_t>(stream), nullptr));
+    return WG_OK;
+}
+
+int wg_profile_apply_mask(wg_handle_t h, void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V,
+                          int64_t row_stride_elems, const uint32_t *d_bitmask, void *stream) {
+    if (!h) return fail(WG_ERR_INVALID, "wg_profile_apply_mask: null handle");
+    if (!h->profiling) return wg_apply_mask(d_logits, dtype, B, V, row_stride_elems, d_bitmask, stream);
+    if (!d_logits || !d_bitmask) return fail(WG_ERR_INVALID, "wg_profile_apply_mask: null argument");
+    if (B == 0 || V == 0 || B > kMaxBatch) return fail(WG_ERR_INVALID, "wg_profile_apply_mask: bad batch or vocabulary size");
+    if (dtype != WG_F32 && dtype != WG_BF16) return fail(WG_ERR_INVALID, "wg_profile_apply_mask: unknown dtype");
+    if (row_stride_elems < (int64_t)V) return fail(WG_ERR_INVALID, "wg_profile_apply_mask: row stride smaller than V");
+    hipEvent_t ev[2];
+    for (auto &e : ev) { e = take_event(h); h->apply_events.push_back(e); }
+    WG_HIP(launch_apply(d_logits, dtype, B, V, row_stride_elems, d_bitmask, static_cast<hipStream_t>(stream), ev));
     return WG_OK;
 }
 
@@ -741,7 +756,11 @@ int wg_profile_read(wg_handle_t h, wg_profile_t *host_out) {
         p.advance_ms += span(h->advance_events[i], h->advance_events[i + 1]);
         p.advance_calls++;
     }
-    for (auto *v : {&h->fill_events, &h->advance_events}) {
+    for (size_t i = 0; i + 1 < h->apply_events.size(); i += 2) {
+        p.apply_ms += span(h->apply_events[i], h->apply_events[i + 1]);
+        p.apply_calls++;
+    }
+    for (auto *v : {&h->fill_events, &h->advance_events, &h->apply_events}) {
         h->spare_events.insert(h->spare_events.end(), v->begin(), v->end());
         v->clear();
     }

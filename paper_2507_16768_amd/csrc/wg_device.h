@@ -130,7 +130,7 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
                        void *logits, int dtype, int64_t logits_stride,
                        uint32_t n_cu, hipStream_t s, hipEvent_t *ev);
 hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
-                        const uint32_t *bitmask, hipStream_t s);
+                        const uint32_t *bitmask, hipStream_t s, hipEvent_t *ev);
 hipError_t launch_masked_argmax(const void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
                                 const uint32_t *bitmask, int32_t *tokens, hipStream_t s);
 // masked top-k: a workgroup ranks kTopkSlice tokens of a row; `lists` is the caller's workspace

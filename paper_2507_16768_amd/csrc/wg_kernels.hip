@@ -1134,27 +1134,27 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
     if (vec) launch(gather_kernel<true>, dim3(cdiv(Vc.W / 4u, 256), B), dim3(256), 0, s, ge, Cc, Vc.W, bitmask);
     else launch(gather_kernel<false>, dim3(cdiv(Vc.W, 256 * 4), B), dim3(256), 0, s, ge, Cc, Vc.W, bitmask);
     // logits that do not allow 16-byte stores take the separate apply kernels
-    if (logits) return launch_apply(logits, dtype, B, Vc.V, logits_stride, bitmask, s);
+    if (logits) return launch_apply(logits, dtype, B, Vc.V, logits_stride, bitmask, s, nullptr);
     return hipGetLastError();
 }
 
 hipError_t launch_apply(void *logits, int dtype, uint32_t B, uint32_t V, int64_t row_stride,
-                        const uint32_t *bitmask, hipStream_t s)
+                        const uint32_t *bitmask, hipStream_t s, hipEvent_t *ev)
 {
     uint32_t W = (V + 31u) / 32u;
     const bool vec_ok = apply_vec_ok(logits, dtype, V, row_stride);
     if (vec_ok) {
         dim3 g(cdiv(V / 8u, 256 * kApplyGroups), B);
         if (dtype == WG_F32)
-            apply_vec_kernel<uint4, 2, uint32_t><<<g, 256, 0, s>>>((uint32_t *)logits, row_stride, V, W, bitmask, 0xFF800000u);
+            launch(apply_vec_kernel<uint4, 2, uint32_t>, g, dim3(256), 0, s, ev, (uint32_t *)logits, row_stride, V, W, bitmask, 0xFF800000u);
         else
-            apply_vec_kernel<uint4, 1, uint16_t><<<g, 256, 0, s>>>((uint16_t *)logits, row_stride, V, W, bitmask, (uint16_t)0xFF80u);
+            launch(apply_vec_kernel<uint4, 1, uint16_t>, g, dim3(256), 0, s, ev, (uint16_t *)logits, row_stride, V, W, bitmask, (uint16_t)0xFF80u);
     } else {
         dim3 g(cdiv(V, 256), B);
         if (dtype == WG_F32)
-            apply_scalar_kernel<uint32_t><<<g, 256, 0, s>>>((uint32_t *)logits, row_stride, V, W, bitmask, 0xFF800000u);
+            launch(apply_scalar_kernel<uint32_t>, g, dim3(256), 0, s, ev, (uint32_t *)logits, row_stride, V, W, bitmask, 0xFF800000u);
         else
-            apply_scalar_kernel<uint16_t><<<g, 256, 0, s>>>((uint16_t *)logits, row_stride, V, W, bitmask, (uint16_t)0xFF80u);
+            launch(apply_scalar_kernel<uint16_t>, g, dim3(256), 0, s, ev, (uint16_t *)logits, row_stride, V, W, bitmask, (uint16_t)0xFF80u);
     }
     return hipGetLastError();
 }
