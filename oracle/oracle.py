@@ -70,6 +70,8 @@ def lib():
         L.wgo_advance.argtypes = [C.c_void_p, C.POINTER(_Vocab), C.c_void_p, C.c_void_p, C.c_uint32]
         L.wgo_key_rem.restype = C.c_uint32
         L.wgo_key_rem.argtypes = [C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32]
+        L.wgo_forced_bytes.restype = C.c_uint32
+        L.wgo_forced_bytes.argtypes = [C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32, C.POINTER(C.c_uint32)]
         L.wgo_select_bit.restype = C.c_int64
         L.wgo_select_bit.argtypes = [C.c_void_p, C.c_uint32, C.c_uint64]
         L.wgo_trajectory.restype = C.c_int64
@@ -181,6 +183,14 @@ class Oracle:
         assert len(tk) == len(st)
         lib().wgo_advance(self.h, C.byref(self.vocab.c), st.ctypes.data, tk.ctypes.data, len(st))
         return st
+
+    def forced_bytes(self, sid, cap=64):
+        """(bytes, state after them): what a request in `sid` can only produce next (the rest of
+        its Write run), at most cap bytes."""
+        buf = (C.c_uint8 * max(cap, 1))()
+        end = C.c_uint32()
+        n = lib().wgo_forced_bytes(self.h, sid, buf, cap, C.byref(end))
+        return bytes(buf[:n]), end.value
 
     def key_rem(self, state, lmax=None):
         return lib().wgo_key_rem(self.h, state[0], state[1],

@@ -801,6 +801,24 @@ uint32_t wgo_key_rem(const wgo_handle *h, uint32_t sid, uint32_t aux, uint32_t l
     return key_rem(h, sid, aux, lmax);
 }
 
+/* The bytes a request in state sid is forced to produce next: a Write is a chain of
+ * checkpoints that each admit one symbol ("a sequence of specialised Wait operators", Mask
+ * Generation and Global Caching), so from a state inside a Write the only walkable
+ * continuation is the rest of that Write -- and of the Writes that follow it directly -- up to
+ * the next state that is not a Write byte (a Wait, a condition, the end of the template).
+ * Writes at most cap bytes to out, returns how many; *end_sid is the state after them (sid
+ * itself when it is not a Write byte, when cap is 0, or when sid is no state at all). */
+uint32_t wgo_forced_bytes(const wgo_handle *h, uint32_t sid, uint8_t *out, uint32_t cap, uint32_t *end_sid)
+{
+    uint32_t n = 0;
+    while (n < cap && sid != WGO_SID_ERROR && sid < h->nleaf && h->leaf[sid].kind == L_LIT) {
+        out[n++] = h->leaf[sid].byte;
+        sid = h->leaf[sid].next;
+    }
+    *end_sid = sid;
+    return n;
+}
+
 /* Index of the k-th (0-based) set bit of the row, or -1. */
 int64_t wgo_select_bit(const uint32_t *row, uint32_t W, uint64_t k)
 {

@@ -465,6 +465,67 @@ def test_budget_key_reduction_is_sound():
         assert (o.mask_row((s, aux)) == o.mask_row((s, 40 - rem))).all()
 
 
+# ---- forced continuation of a Write run (jump-forward) ---------------------------------------
+
+def test_forced_bytes_of_a_hand_worked_tree():
+    text = """
+    Sequence(
+      Write("ab"),
+      Wait(allow={x}, wait={;}, body=Write("c")),
+      IfElse(condition=Wait(allow={}, true_waits={t}, false_waits={f}),
+             if_body=Write("T"), else_body=None),
+      DoWhile(body=Sequence(Write(""), Write("d")),
+              condition=Wait(allow={}, true_waits={+}, false_waits={.})),
+      Write("")
+    )"""
+    o = O.Oracle([text, 'Sequence(Write("zq"), Write("r"))'])
+    # ids: 1 a, 2 b, 3 Wait, 4 c, 5 cond, 6 T, 7 d, 8 loop cond, 9 END; template 1: 10 z, 11 q, 12 r, 13 END
+    assert o.forced_bytes(1) == (b"ab", 3)                 # up to the Wait
+    assert o.forced_bytes(2) == (b"b", 3)
+    assert o.forced_bytes(3) == (b"", 3)                   # a Wait forces nothing
+    assert o.forced_bytes(4) == (b"c", 5)                  # the Wait's body, then the condition
+    assert o.forced_bytes(5) == (b"", 5)
+    assert o.forced_bytes(6) == (b"Td", 8)                 # if_body runs on into the loop body
+    assert o.forced_bytes(7) == (b"d", 8)
+    assert o.forced_bytes(9) == (b"", 9)                   # END: only <eos> follows, no byte
+    assert o.forced_bytes(10) == (b"zqr", 13)              # two Writes in a row are one run
+    assert o.forced_bytes(10, cap=2) == (b"zq", 12)        # cut at cap: the state after what was written
+    assert o.forced_bytes(10, cap=0) == (b"", 10)
+    assert o.forced_bytes(0) == (b"", 0)
+    assert o.forced_bytes(O.SID_ERROR) == (b"", O.SID_ERROR)
+    assert o.forced_bytes(77) == (b"", 77)
+
+
+@pytest.mark.parametrize("restart", [False, True])
+def test_forced_bytes_are_the_only_walkable_continuation(restart):
+    """Brute force on random trees: from every reachable state, each forced byte is the one symbol
+    of the 257 the machine accepts there, the structural interpreter (no numbering, no state
+    table) agrees on the prefix that led to the state, the run ends in the state the walk ends
+    in, and that state is not a Write byte: the run is neither too short nor too long."""
+    rng = Counter(13, 2, start=5000 * restart)
+    seen_runs = 0
+    for case in range(80):
+        tree = TreeGen(rng, alphabet=ALPHA, max_depth=2, write_len=(0, 4), big=False).tree(2, 16)
+        o = O.Oracle([ws.to_text(tree)], None, None, restart=restart)
+        for st, pre in _reach_states(o, tree, rng, 10, restart):
+            run, end = o.forced_bytes(st[0])
+            kind = o.describe(st[0])["kind"] if st[0] < o.num_states else None
+            assert (len(run) > 0) == (kind == "LIT")
+            cur = st
+            for i, y in enumerate(run):
+                accepted = [x for x in range(257) if o.step(cur[0], cur[1], x) is not None]
+                assert accepted == [y], (ws.to_text(tree), pre, run, i)
+                for x in list(ALPHA) + [EOS]:              # the interpreter that knows no state ids
+                    assert brute.walkable(tree, pre + list(run[:i]) + [x], restart) == (x == y)
+                cur = o.step(cur[0], cur[1], y)
+            assert cur[0] == end
+            assert end >= o.num_states or o.describe(end)["kind"] != "LIT"
+            if len(run) > 1:                                # a cap cuts the run, it does not change it
+                assert o.forced_bytes(st[0], cap=len(run) - 1) == (run[:-1], o.walk_bytes(st, run[:-1])[0])
+            seen_runs += len(run) > 0
+    assert seen_runs > 100
+
+
 # ---- conventions: numbering, restart, errors (self-consistency only) ------------------------
 
 def test_canonical_numbering_of_a_hand_worked_tree():
