@@ -276,6 +276,19 @@ int wg_masked_topk_static(const void *d_logits, wg_dtype_t dtype, uint32_t B, ui
 int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B,
                void *stream);
 
+/* wg_forced_bytes (jump-forward): what request b can only produce next.  A Write is a chain of
+ * checkpoints that each admit one symbol (section "Mask Generation and Global Caching": Write
+ * as a sequence of specialised Waits), so from a state inside a Write the continuation is fixed
+ * up to the next Wait, condition or end of the template, and an engine may append those bytes
+ * without sampling them.  d_bytes[b][0 .. d_lens[b]) receives the rest of the request's Write and
+ * of the Writes that follow it directly, cut at cap bytes (d_bytes is [B][cap] uint8, d_lens [B]
+ * uint32); d_lens[b] is 0 for a state that is not a Write byte (also ERROR and out-of-range
+ * states).  d_end_states[b] (may be NULL) receives the state after those bytes: feeding them
+ * through wg_advance as tokens leads to the same state; a request with nothing forced keeps its
+ * state, aux included.  The states themselves are only read.  One kernel, enqueued on `stream`. */
+int wg_forced_bytes(wg_handle_t h, const wg_state_t *d_states, uint32_t B, uint32_t cap,
+                    uint8_t *d_bytes, uint32_t *d_lens, wg_state_t *d_end_states, void *stream);
+
 /* wg_advance_fill_masks: wg_advance followed by wg_fill_masks on the new states, for the decode
  * loop, where the two always meet (the token sampled under step k's mask is consumed, then step
  * k+1's mask is produced): same results, one kernel launch and one pass over the state

@@ -58,7 +58,7 @@ EXPORTS = [
     "wg_add_instances", "wg_num_instances", "wg_cache_resize", "wg_table_add_instances",
     "wg_table_num_instances", "wg_advance_fill_masks", "wg_regex_to_template",
     "wg_decode_step", "wg_masked_topk", "wg_masked_topk_workspace", "wg_reserve_batch", "wg_max_batch",
-    "wg_masked_topk_static", "wg_masked_topk_static_capacity", "wg_profile_apply_mask",
+    "wg_masked_topk_static", "wg_masked_topk_static_capacity", "wg_profile_apply_mask", "wg_forced_bytes",
 ]
 
 
@@ -120,6 +120,7 @@ def load_library():
     L.wg_masked_topk_static_capacity.argtypes = []
     L.wg_masked_topk_static_capacity.restype = u64
     L.wg_masked_topk_static.argtypes = [vp, C.c_int, u32, u32, i64, vp, u32, vp, vp, vp]
+    L.wg_forced_bytes.argtypes = [vp, vp, u32, u32, vp, vp, vp, vp]
     L.wg_cache_clear.argtypes = [vp, vp]
     L.wg_cache_stats.argtypes = [vp, C.POINTER(_Stats)]
     L.wg_error_count.argtypes = [vp, C.POINTER(u64)]
@@ -314,6 +315,19 @@ class Handle:
             None if tokens is None else _dev(tokens, torch.int32, "tokens"), B,
             _dev(bitmask, torch.int32, "bitmask"), C.c_void_p(logits.data_ptr()), dt, logits.stride(0),
             _stream_ptr(stream)))
+
+    def forced_bytes(self, states, out_bytes, out_lens, end_states=None, stream=None):
+        """wg_forced_bytes: out_bytes uint8 [B, cap], out_lens int32 [B], end_states int32 [B, 2] or None."""
+        import torch
+        B = states.shape[0]
+        if tuple(states.shape) != (B, 2) or out_bytes.dim() != 2 or out_bytes.shape[0] != B or tuple(out_lens.shape) != (B,):
+            raise ValueError("states must be [B, 2], out_bytes [B, cap] and out_lens [B]")
+        if end_states is not None and tuple(end_states.shape) != (B, 2):
+            raise ValueError("end_states must be [B, 2]")
+        _check(load_library().wg_forced_bytes(
+            self._h, _dev(states, torch.int32, "states"), B, out_bytes.shape[1],
+            _dev(out_bytes, torch.uint8, "out_bytes"), _dev(out_lens, torch.int32, "out_lens"),
+            None if end_states is None else _dev(end_states, torch.int32, "end_states"), _stream_ptr(stream)))
 
     def add_instances(self, texts, args, stream=None, marshalled=None):
         """wg_add_instances: returns the start states [n, 2] of the new instances.  `marshalled`

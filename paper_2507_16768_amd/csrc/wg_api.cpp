@@ -28,12 +28,14 @@ struct wg_vocab_s {
     uint8_t *d_bytes = nullptr, *d_len8 = nullptr;
     uint32_t *d_offsets = nullptr, *d_lit_start = nullptr, *d_len_rows = nullptr;
     uint64_t *d_chunks = nullptr;
-    ExitEntry *d_lit_entries = nullptr;
+    ExitEntry *d_lit_entries = nullptr, *d_sorted = nullptr, *d_bigram = nullptr;
+    uint32_t *d_dir0 = nullptr, *d_dirN = nullptr;
     int device = 0;
     void release() {
         (void)hipFree(d_bytes); (void)hipFree(d_len8); (void)hipFree(d_offsets);
         (void)hipFree(d_lit_start); (void)hipFree(d_len_rows); (void)hipFree(d_chunks);
-        (void)hipFree(d_lit_entries);
+        (void)hipFree(d_lit_entries); (void)hipFree(d_sorted); (void)hipFree(d_bigram);
+        (void)hipFree(d_dir0); (void)hipFree(d_dirN);
     }
 };
 
@@ -45,10 +47,12 @@ struct wg_handle_s {
     // device copies of the table, with room to append (capacities in elements)
     StateDesc *d_states = nullptr;
     uint8_t *d_classes = nullptr, *d_lit = nullptr;
+    ClassInfo *d_class_info = nullptr;
     uint32_t cap_states = 0, cap_classes = 0, cap_keys = 0;
     uint32_t up_states = 0, up_classes = 0;           // how much of the host table is on the device
     // class index storage: one buffer of V exit entries per class table in use, and the
     // device table of their addresses
+    std::vector<ClassInfo> class_info;                // host copy, kept for the asynchronous uploads
     std::vector<ExitEntry *> class_bufs;
     std::vector<ExitEntry *> class_slabs;             // what was allocated: class_bufs point into these
     uint32_t slab_left = 0;                           // class buffers not handed out yet in the last slab
@@ -128,6 +132,21 @@ template <class T> int regrow(T **p, size_t keep_n, size_t new_n, size_t pad_byt
     return WG_OK;
 }
 
+ClassInfo class_info_of(const uint8_t *table) {
+    ClassInfo ci{};
+    uint32_t n_a = 0, n_b = 0, live = 0;
+    for (uint32_t x = 0; x < 256; x++) {
+        const uint8_t c = table[x];
+        live += c != CLS_REJECT;
+        if (c == CLS_EXIT_A) { if (n_a < kMaxExitBytes) ci.a[n_a] = (uint8_t)x; n_a++; }
+        if (c == CLS_EXIT_B) { if (n_b < kMaxExitBytes) ci.b[n_b] = (uint8_t)x; n_b++; }
+    }
+    ci.n_a = n_a > kMaxExitBytes ? kManyExits : (uint8_t)n_a;
+    ci.n_b = n_b > kMaxExitBytes ? kManyExits : (uint8_t)n_b;
+    ci.flags = live <= 64 ? CI_REJECT_HEAVY : 0;
+    return ci;
+}
+
 uint32_t grown(uint32_t need, uint32_t floor_n) {
     uint64_t n = need < floor_n ? floor_n : need;
     n += n / 2;                                        // headroom for instances added later
@@ -161,11 +180,12 @@ int sync_table(wg_handle_s *h, hipStream_t s) {
     if (n_classes > h->cap_classes) {
         const uint32_t nc = grown(n_classes, 64);
         int rc = regrow(&h->d_classes, (size_t)h->up_classes * 256, (size_t)nc * 256);
+        if (rc == WG_OK) rc = regrow(&h->d_class_info, h->up_classes, nc);
         if (rc == WG_OK) rc = regrow(&h->dc.class_built, h->cap_classes, nc);
         // one pair of counters per class table, 128 bytes apart so that appends to different
         // tables do not meet in one cache line
         if (rc == WG_OK) rc = regrow(&h->dc.class_count, (size_t)h->cap_classes * 32, (size_t)nc * 32);
-        if (rc == WG_OK) rc = regrow(&h->dc.class_rows, (size_t)h->cap_classes * 2 * row_stride, (size_t)nc * 2 * row_stride);
+        if (rc == WG_OK) rc = regrow(&h->dc.class_rows, (size_t)h->cap_classes * 3 * row_stride, (size_t)nc * 3 * row_stride);
         if (rc == WG_OK) rc = regrow(&h->d_class_entries, h->cap_classes, nc);
         if (rc != WG_OK) return rc;
         h->cap_classes = nc;
@@ -180,6 +200,9 @@ int sync_table(wg_handle_s *h, hipStream_t s) {
         const uint32_t a = h->up_classes, n = n_classes - a;
         WG_HIP(hipMemcpyAsync(h->d_classes + (size_t)a * 256, t.classes.data() + (size_t)a * 256, (size_t)n * 256,
                               hipMemcpyHostToDevice, s));
+        h->class_info.resize(n_classes);
+        for (uint32_t c = a; c < n_classes; c++) h->class_info[c] = class_info_of(t.classes.data() + (size_t)c * 256);
+        WG_HIP(hipMemcpyAsync(h->d_class_info + a, h->class_info.data() + a, n * sizeof(ClassInfo), hipMemcpyHostToDevice, s));
         // Per class table: V slots for the list of the whole table, V for the lists of its token
         // ranges.  The buffers are cut from slabs of several, so that an instance which brings
         // one new table does not pay for a device allocation of its own.
@@ -207,7 +230,7 @@ int sync_table(wg_handle_s *h, hipStream_t s) {
         h->up_states = n_states;
         h->up_classes = n_classes;
     }
-    h->dt = DeviceTable{h->d_states, h->d_classes, h->d_lit, n_states, t.lmax, n_classes};
+    h->dt = DeviceTable{h->d_states, h->d_classes, h->d_class_info, h->d_lit, n_states, t.lmax, n_classes};
     h->dc.class_entries = h->d_class_entries;
     h->dc.n_keys = t.n_keys;
     return WG_OK;
@@ -323,6 +346,49 @@ int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uin
             lit_entries[i] = e;
         }
     }
+    // The vocabulary in byte order (the prefix-indexed view of it): a literal state admits the
+    // tokens that are prefixes of the bytes still to be written and the tokens that go on
+    // after them, and both lie in the range of tokens sharing the literal's first two bytes.
+    std::vector<ExitEntry> sorted;
+    std::vector<uint32_t> dir0(256 * 257 + 1, 0);
+    {
+        std::vector<uint32_t> order;
+        order.reserve(V);
+        for (uint32_t t = 0; t < V; t++) if (len8[t]) order.push_back(t);
+        std::sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) {
+            const uint32_t la = len8[a], lb = len8[b];
+            const int c = std::memcmp(bytes.data() + off[a], bytes.data() + off[b], la < lb ? la : lb);
+            return c != 0 ? c < 0 : la != lb ? la < lb : a < b;
+        });
+        sorted.resize(order.size() ? order.size() : 1);
+        auto range_of = [&](uint32_t t) {
+            return (uint32_t)bytes[off[t]] * 257u + (len8[t] > 1 ? 1u + bytes[off[t] + 1] : 0u);
+        };
+        for (size_t i = 0; i < order.size(); i++) {
+            const uint32_t t = order[i];
+            ExitEntry e;
+            e.tok = t; e.off = 0; e.cls = 0; e.first = len8[t] > 1 ? bytes[off[t] + 1] : 0; e.rem = len8[t];
+            sorted[i] = e;
+            dir0[range_of(t) + 1u]++;
+        }
+        for (uint32_t y = 0; y < 256 * 257; y++) dir0[y + 1] += dir0[y];
+    }
+    // Every byte pair inside a token, grouped by the pair: a checkpoint whose exit byte e leads to
+    // a literal byte y can only be left early by tokens in which y follows e.
+    std::vector<uint32_t> dirN(65536 + 1, 0);
+    for (uint32_t t = 0; t < V; t++)
+        for (uint32_t i = 1; i < len8[t]; i++) dirN[((uint32_t)bytes[off[t] + i - 1] << 8 | bytes[off[t] + i]) + 1u]++;
+    for (uint32_t y = 0; y < 65536; y++) dirN[y + 1] += dirN[y];
+    std::vector<ExitEntry> bigram(dirN[65536] ? dirN[65536] : 1);
+    {
+        std::vector<uint32_t> at(dirN.begin(), dirN.end() - 1);
+        for (uint32_t t = 0; t < V; t++)
+            for (uint32_t i = 1; i < len8[t]; i++) {
+                ExitEntry e;
+                e.tok = t; e.off = (uint8_t)i; e.cls = 0; e.first = bytes[off[t] + i]; e.rem = (uint8_t)(len8[t] - i);
+                bigram[at[(uint32_t)bytes[off[t] + i - 1] << 8 | bytes[off[t] + i]]++] = e;
+            }
+    }
     hipError_t e = upload(&v->d_bytes, bytes.data(), bytes.size());
     if (e == hipSuccess) e = upload(&v->d_offsets, off.data(), off.size());
     if (e == hipSuccess) e = upload(&v->d_len8, len8.data(), len8.size());
@@ -330,13 +396,18 @@ int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uin
     if (e == hipSuccess) e = upload(&v->d_lit_entries, lit_entries.data(), lit_entries.size());
     if (e == hipSuccess) e = upload(&v->d_lit_start, lit_start.data(), lit_start.size());
     if (e == hipSuccess) e = upload(&v->d_len_rows, len_rows.data(), len_rows.size());
+    if (e == hipSuccess) e = upload(&v->d_sorted, sorted.data(), sorted.size());
+    if (e == hipSuccess) e = upload(&v->d_dir0, dir0.data(), dir0.size());
+    if (e == hipSuccess) e = upload(&v->d_bigram, bigram.data(), bigram.size());
+    if (e == hipSuccess) e = upload(&v->d_dirN, dirN.data(), dirN.size());
     if (e != hipSuccess) {
         v->release();
         return fail(e == hipErrorOutOfMemory ? WG_ERR_NOMEM : WG_ERR_HIP,
                     std::string("wg_vocab_create: ") + hipGetErrorString(e));
     }
     v->dv = DeviceVocab{v->d_bytes, v->d_offsets, v->d_len8, v->d_chunks, v->d_lit_entries,
-                        v->d_lit_start, v->d_len_rows, V, W, eos_id, lmax, n_chunks, rs, {}};
+                        v->d_lit_start, v->d_len_rows, v->d_sorted, v->d_dir0, v->d_bigram, v->d_dirN,
+                        V, W, eos_id, lmax, n_chunks, rs, {}};
     for (uint32_t p = 0; p <= kParts; p++) v->dv.part_tok[p] = part_tok[p];
     *out = v.release();
     return WG_OK;
@@ -434,7 +505,7 @@ void wg_table_destroy(wg_table_t t) { delete t; }
 void wg_destroy(wg_handle_t h) {
     if (!h) return;
     (void)hipDeviceSynchronize();
-    (void)hipFree(h->d_states); (void)hipFree(h->d_classes); (void)hipFree(h->d_lit);
+    (void)hipFree(h->d_states); (void)hipFree(h->d_classes); (void)hipFree(h->d_lit); (void)hipFree(h->d_class_info);
     (void)hipFree(h->dc.ctr); (void)hipFree(h->dc.tags); (void)hipFree(h->dc.arena);
     (void)hipFree(h->dc.row_ref); (void)hipFree(h->dc.miss); (void)hipFree(h->dc.class_miss);
     (void)hipFree(h->dc.class_built); (void)hipFree(h->dc.class_rows);
@@ -486,7 +557,7 @@ int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_t
     size_t free_b = 0, total_b = 0;
     WG_HIP(hipMemGetInfo(&free_b, &total_b));
     const uint64_t n_classes = t.classes.size() / 256;
-    const uint64_t class_bytes = n_classes * (2ull * row_bytes + 2ull * vocab->dv.V * sizeof(ExitEntry));
+    const uint64_t class_bytes = n_classes * (3ull * row_bytes + 2ull * vocab->dv.V * sizeof(ExitEntry));
     if (class_bytes > (uint64_t)free_b / 4)
         return fail(WG_ERR_NOMEM, "wg_compile: the class indexes (" + std::to_string(class_bytes >> 20) +
                                       " MiB for " + std::to_string(n_classes) +
@@ -697,6 +768,14 @@ int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uin
     return WG_OK;
 }
 
+int wg_forced_bytes(wg_handle_t h, const wg_state_t *d_states, uint32_t B, uint32_t cap, uint8_t *d_bytes,
+                    uint32_t *d_lens, wg_state_t *d_end_states, void *stream) {
+    if (!h || !d_states || !d_bytes || !d_lens) return fail(WG_ERR_INVALID, "wg_forced_bytes: null argument");
+    if (B == 0 || cap == 0) return fail(WG_ERR_INVALID, "wg_forced_bytes: B or cap is 0");
+    WG_HIP(launch_forced_bytes(h->dt, d_states, B, cap, d_bytes, d_lens, d_end_states, static_cast<hipStream_t>(stream)));
+    return WG_OK;
+}
+
 int wg_cache_clear(wg_handle_t h, void *stream) {
     if (!h) return fail(WG_ERR_INVALID, "wg_cache_clear: null handle");
     // The generation number travels with every later launch as a kernel argument, so the
@@ -719,7 +798,7 @@ int wg_cache_stats(wg_handle_t h, wg_cache_stats_t *host_out) {
     const uint64_t row_bytes = (uint64_t)h->dc.row_stride * 4ull;
     host_out->arena_bytes = (uint64_t)h->dc.cap_rows * row_bytes +
                             (uint64_t)(h->class_bufs.size() + h->slab_left) * (2ull * h->vocab->dv.V * sizeof(ExitEntry)) +
-                            (uint64_t)h->cap_classes * 2ull * row_bytes;
+                            (uint64_t)h->cap_classes * 3ull * row_bytes;
     return WG_OK;
 }
 

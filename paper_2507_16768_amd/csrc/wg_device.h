@@ -15,9 +15,23 @@ constexpr uint32_t kNoKey = 0xFFFFFFFFu;
 constexpr uint32_t kParts = 8;
 constexpr uint32_t kPartGroup = 1024;
 
+// What the kernels want to know about a class table without reading its 256 bytes: the bytes
+// that leave through exit A / exit B (as long as there are at most kMaxExitBytes of them on a
+// side), and whether most byte values are rejected.
+constexpr uint32_t kMaxExitBytes = 6;
+struct ClassInfo {
+    uint8_t n_a, n_b;            // bytes of class EXIT_A / EXIT_B, or 0xFF: more than kMaxExitBytes
+    uint8_t flags, pad;
+    uint8_t a[kMaxExitBytes], b[kMaxExitBytes];
+};
+static_assert(sizeof(ClassInfo) == 16, "class info layout");
+enum : uint8_t { CI_REJECT_HEAVY = 1 };    // at most 64 byte values are not rejected
+constexpr uint8_t kManyExits = 0xFF;
+
 struct DeviceTable {
     const StateDesc *states;
     const uint8_t *classes;      // 256-byte class tables
+    const ClassInfo *class_info; // one per class table
     const uint8_t *lit;          // literal byte per state
     uint32_t n_states;
     uint32_t lmax;
@@ -41,6 +55,17 @@ struct DeviceVocab {
     const ExitEntry *lit_entries;   // tokens grouped by (first byte, range): a literal state's candidates
     const uint32_t *lit_start;   // 256 * kParts + 1 bucket boundaries into lit_entries
     const uint32_t *len_rows;    // row r (0 .. lmax+1): tokens with 1 <= length <= r
+    // The vocabulary in byte order (tokens that have bytes, compared as byte strings), as
+    // entries {tok, off = 0, first = second byte, rem = length}, with the ranges of its one- and
+    // two-byte prefixes: range y0 * 257 of dir0 holds the token that is the single byte y0,
+    // range y0 * 257 + 1 + y1 the tokens of two or more bytes that start with y0 y1.
+    const ExitEntry *sorted;
+    const uint32_t *dir0;        // 256 * 257 + 1 boundaries into sorted
+    // Every place inside a token where one byte follows another: entries {tok, off = index of the
+    // second byte, first = that byte, rem = bytes from it to the end}, grouped by the byte pair;
+    // range e * 256 + y of dirN holds the places where y follows e.
+    const ExitEntry *bigram;
+    const uint32_t *dirN;        // 65536 + 1 boundaries into bigram
     uint32_t V, W;
     int32_t eos_id;
     uint32_t lmax;
@@ -59,13 +84,25 @@ struct MissEntry {
     uint32_t key, sid, aux, kind;
     uint32_t r;                  // allow-bytes that may still be consumed, capped at lmax
     uint32_t cls;                // WAIT / COND: class table id
-    uint32_t lit, pad0;          // LIT: the byte (its first-byte buckets hold the candidates)
+    uint32_t lit;                // LIT: the byte (its first-byte buckets hold the candidates)
+    uint8_t mode;                // KB_*: where the candidate tokens of the key come from
+    uint8_t n_a, n_b, pad0;      // KB_BIGRAM: how many exit bytes of each side are listed
     uint32_t eos_next, next_a, next_b;
     uint32_t slot;               // arena row of the result, or kNoSlot: only into the bitmask row of `req`
     uint32_t req;                // the request that claimed the key
-    uint32_t pad[3];
+    uint32_t exits[3];           // KB_BIGRAM: byte k of these 12 is exit byte k of side A (k < 6) or k - 6 of side B
     HopState hop[2];             // successors reached through exit A / exit B
 };
+// Where key_build finds the tokens that can leave the key's state before their last byte:
+//   KB_LIST   the exit list of the state's class table, or the first-byte buckets of a literal
+//             state: every entry is looked at (and, for a key whose successor is a checkpoint,
+//             walked; such a key is cut into one work item per token range);
+//   KB_SORTED a literal state followed by another literal byte, or by nothing that takes a byte:
+//             the tokens that start with those two bytes, and the one-byte token, from the
+//             vocabulary in byte order;
+//   KB_BIGRAM a checkpoint whose exits lead to literal bytes (or to the end): the places in the
+//             vocabulary where an exit byte is followed by the literal byte.
+enum : uint8_t { KB_LIST = 0, KB_SORTED = 1, KB_BIGRAM = 2 };
 static_assert(sizeof(MissEntry) == 112, "miss entry layout");
 
 struct Counters {
@@ -105,7 +142,7 @@ struct DeviceCache {
     uint32_t cap_rows;
     // per class table (the context-free part of every mask of a state using that table)
     uint32_t *class_built;       // generation in which the class index was built
-    uint32_t *class_rows;        // 2 rows per class: [stay] all bytes stay, [end] exits on its last byte
+    uint32_t *class_rows;        // 3 rows per class: [stay] all bytes stay, [end] exits on its last byte, [both]
     ExitEntry *const *class_entries;   // per class 2 V slots: [0, V) the list of the class table, range p of
                                  // the second V owns [V + part_tok[p], V + part_tok[p+1]); each filled
                                  // from both ends
@@ -148,6 +185,8 @@ hipError_t static_topk_scratch(unsigned long long **out);
 hipError_t launch_advance(const DeviceTable &T, const DeviceVocab &Vc, const DeviceCache &Cc,
                           wg_state_t *states, const int32_t *tokens, uint32_t B, hipStream_t s,
                           hipEvent_t *ev);
+hipError_t launch_forced_bytes(const DeviceTable &T, const wg_state_t *states, uint32_t B, uint32_t cap,
+                               uint8_t *bytes, uint32_t *lens, wg_state_t *end_states, hipStream_t s);
 hipError_t launch_select(const uint32_t *bitmask, uint32_t B, uint32_t V, const uint64_t *draws,
                          int32_t *tokens, hipStream_t s);
 hipError_t configure_kernels(uint32_t row_bytes);

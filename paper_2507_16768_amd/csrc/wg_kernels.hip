@@ -171,6 +171,7 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceCac
     const uint32_t rows0 = env.rows0;
     uint32_t ref = kNoKey;
     StateDesc d{}, dn[2] = {};
+    ClassInfo ci{};
     uint32_t class_gen = 0;
     if (live) {
         if (sid < T.n_states) {
@@ -187,8 +188,9 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceCac
             // from clamped indexes, so that nothing waits for them before the tag has decided.
             dn[0] = T.states[d.next_a < T.n_states ? d.next_a : 0u];
             dn[1] = T.states[d.next_b < T.n_states ? d.next_b : 0u];
-            class_gen = __hip_atomic_load(&Cc.class_built[(kind == WG_KIND_WAIT || kind == WG_KIND_COND) ? d.cls : 0u],
-                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t own_class = (kind == WG_KIND_WAIT || kind == WG_KIND_COND) ? d.cls : 0u;
+            class_gen = __hip_atomic_load(&Cc.class_built[own_class], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ci = T.class_info[own_class];
             // anything but a row of this generation or a claim made in this very call is stale
             hit = (uint32_t)(t >> 32) == epoch;
             const bool this_call = t >= kTagClaim && ((t >> 16) & kTagLaunchMask) == launch;
@@ -239,6 +241,23 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceCac
             me.slot = slot; me.req = b;
             me.hop[0] = hop[0]; me.hop[1] = hop[1];
             me.lit = (d.kind_byte >> 8) & 0xFFu;
+            // Where the candidates come from.  A key that is not deep has, behind each exit, a
+            // literal byte or a state that takes no byte at all: its candidates are found in
+            // the static indexes of the vocabulary by the bytes involved (tokens of at most 24
+            // bytes: the walkers of those paths hold a token in registers).
+            me.mode = KB_LIST;
+            if (!deep && T.lmax <= 24u) {
+                const bool lit0 = hop[0].kind == WG_KIND_LIT, lit1 = hop[1].kind == WG_KIND_LIT;
+                if (kind == WG_KIND_LIT) me.mode = KB_SORTED;
+                else if ((kind == WG_KIND_WAIT || kind == WG_KIND_COND) &&
+                         (!lit0 || ci.n_a != kManyExits) && (!lit1 || ci.n_b != kManyExits)) {
+                    me.mode = KB_BIGRAM;
+                    me.n_a = lit0 ? ci.n_a : 0; me.n_b = lit1 ? ci.n_b : 0;
+                    me.exits[0] = ci.a[0] | ci.a[1] << 8 | ci.a[2] << 16 | (uint32_t)ci.a[3] << 24;
+                    me.exits[1] = ci.a[4] | ci.a[5] << 8 | ci.b[0] << 16 | (uint32_t)ci.b[1] << 24;
+                    me.exits[2] = ci.b[2] | ci.b[3] << 8 | ci.b[4] << 16 | (uint32_t)ci.b[5] << 24;
+                }
+            }
             Cc.miss[deep ? first_deep + (uint32_t)__popcll(dm & below)
                          : Cc.miss_cap - 1u - (first_plain + (uint32_t)__popcll(pm & below))] = me;
             if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
@@ -279,10 +298,13 @@ lookup_kernel(DeviceTable T, DeviceCache Cc, const wg_state_t *__restrict__ stat
 // class.  Results: row [stay] = tokens whose bytes all stay, row [end] = tokens that exit on
 // their last byte, and one ExitEntry per token that exits earlier.
 //
-// A workgroup handles one (class table, 1024-token group): the 256-byte table sits in LDS,
+// A workgroup handles one (class table, 1024-token group): the 256-byte table sits in LDS and
 // every lane owns 4 tokens (one in each of its wavefront's 4 slices of 64) whose lengths and
-// 8-byte chunks are all requested before any is used, so the loads overlap.  Exit entries are
-// appended with one atomic per workgroup.
+// first 8-byte chunks are requested before the table is known.  A first pass decides what the
+// first chunk can decide (for a table that rejects most byte values: what the first byte can
+// decide); the tokens that need more are queued in LDS and finished by a second pass on full
+// wavefronts.  Rows and exit entries are assembled in LDS and leave in whole runs; the places
+// of the entries in the global lists are taken with four atomics per workgroup.
 
 // Classifies up to 8 bytes of one chunk.  Returns true once the token is decided.
 __device__ __forceinline__ bool scan_chunk(const uint8_t *lut, uint64_t cb, uint32_t L, uint32_t k,
@@ -308,16 +330,40 @@ __device__ __forceinline__ bool scan_chunk(const uint8_t *lut, uint64_t cb, uint
     return false;
 }
 
+// Appends the early exits of a wavefront's tokens to the workgroup's staging list in LDS: those
+// with a short remainder from the front, the others from the back (a token leaves at most one
+// entry, so the two ends cannot meet); one LDS atomic per wavefront and end.
+__device__ __forceinline__ void stage_entry(uint2 *ent, uint32_t *n_ent, bool early, uint32_t tok, uint32_t nx,
+                                            uint32_t res, uint32_t first, uint32_t rem)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const bool is_long = rem > kShortRem;
+    const unsigned long long bx = __ballot(early && !is_long), by = __ballot(early && is_long);
+    if (!(bx | by)) return;
+    uint32_t b0 = 0, b1 = 0;
+    if (lane == 0) {
+        if (bx) b0 = atomicAdd(&n_ent[0], (uint32_t)__popcll(bx));
+        if (by) b1 = atomicAdd(&n_ent[1], (uint32_t)__popcll(by));
+    }
+    b0 = __shfl(b0, 0); b1 = __shfl(b1, 0);
+    if (early) {
+        const uint32_t rank = (uint32_t)__popcll((is_long ? by : bx) & ((1ull << lane) - 1ull));
+        ent[is_long ? kScanGroup - 1u - (b1 + rank) : b0 + rank] = uint2{tok, nx | res << 8 | first << 16 | rem << 24};
+    }
+}
+
 __global__ void __launch_bounds__(256)
 class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lut[256];
-    __shared__ uint32_t seg[2][16];                  // short / long entries per (wave, slice)
-    __shared__ uint32_t seg_pre[2][16];              // ... summed up: where each (wave, slice) starts within the workgroup
-    __shared__ uint32_t seg_base[2][2];              // where this workgroup's entries start in the two lists
+    __shared__ uint32_t row_s[kScanGroup / 32u], row_e[kScanGroup / 32u];   // the group's words of the two rows
+    __shared__ uint2 ent[kScanGroup];                // early exits of the group, from both ends
+    __shared__ uint32_t que[kScanGroup];             // tokens the first pass could not decide
+    __shared__ uint32_t n_ent[2], n_que;
+    __shared__ uint32_t list_base[2][2];             // where this workgroup's entries start in the two lists
     const uint32_t n = Cc.ctr->n_class_miss;
     const uint32_t groups = (Vc.V + kScanGroup - 1u) / kScanGroup;
-    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6, tid = threadIdx.x;
     const uint32_t V = Vc.V;
     // Workgroups are handed to the 8 XCDs round-robin and each XCD has its own L2.  XCD x takes
     // the token groups g with g % 8 == x for every class table, so a group's bytes are fetched
@@ -334,17 +380,12 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
     const uint32_t c_first = Cc.class_miss[ci_first < Cc.miss_cap ? ci_first : 0u];   // the list has miss_cap places
     for (uint64_t item = local; item < total; item += local_wgs) {
         const uint32_t ci = (uint32_t)(item / my_groups);
-        const uint32_t c = item == local ? c_first : Cc.class_miss[ci];
         const uint32_t g = (uint32_t)(item % my_groups) * nx + xcd;
-        uint32_t part = 0;
-#pragma unroll
-        for (uint32_t q = 1; q < kParts; q++) part += g * kScanGroup >= Vc.part_tok[q];
-        __syncthreads();
-        if (threadIdx.x < 64u)
-            reinterpret_cast<uint32_t *>(lut)[threadIdx.x] =
-                reinterpret_cast<const uint32_t *>(T.classes + (size_t)c * 256u)[threadIdx.x];
+        // The tokens do not depend on the table: their lengths and first chunks are requested
+        // before the table is known.  A lane owns 4 tokens, one in each of its wavefront's 4
+        // slices of 64, so that a ballot over a slice is two words of a row.
         uint32_t tk[4], L[4];
-        uint64_t c0[4], c1[4], c2[4];
+        uint64_t c0[4];
 #pragma unroll
         for (int s = 0; s < 4; s++) {
             tk[s] = g * kScanGroup + (wave * 4u + s) * 64u + lane;
@@ -352,92 +393,125 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
             L[s] = valid ? Vc.len8[tk[s]] : 0u;
             c0[s] = valid ? Vc.chunks[tk[s]] : 0ull;
         }
+        const uint32_t c = item == local ? c_first : Cc.class_miss[ci];
+        uint32_t part = 0;
 #pragma unroll
-        for (int s = 0; s < 4; s++) {
-            // requested regardless of the length (chunks past a token's end are zero), so that
-            // no load waits for another
-            const bool valid = tk[s] < V;
-            c1[s] = valid && Vc.n_chunks > 1u ? Vc.chunks[(size_t)V + tk[s]] : 0ull;
-            c2[s] = valid && Vc.n_chunks > 2u ? Vc.chunks[2ull * V + tk[s]] : 0ull;
-        }
+        for (uint32_t q = 1; q < kParts; q++) part += g * kScanGroup >= Vc.part_tok[q];
+        __syncthreads();                             // the item before is done with the LDS
+        if (tid < 64u)
+            reinterpret_cast<uint32_t *>(lut)[tid] = reinterpret_cast<const uint32_t *>(T.classes + (size_t)c * 256u)[tid];
+        if (tid == 0) { n_ent[0] = 0; n_ent[1] = 0; n_que = 0; }
+        // A table that rejects most byte values decides most tokens by their first byte: the
+        // first pass looks at that byte only.
+        const bool heavy = (T.class_info[c].flags & CI_REJECT_HEAVY) != 0;
         __syncthreads();
-        uint32_t *row_stay = Cc.class_rows + (size_t)(2u * c) * Cc.row_stride;
-        uint32_t *row_end = row_stay + Cc.row_stride;
-        uint32_t res[4], j[4];
-        unsigned long long bx[4], by[4], stay_bits[4], end_bits[4];
+        // First pass, every token: its first 8 bytes (its first byte, for a rejecting table).
+        // A token that needs more -- bytes beyond the first chunk, or any further look for a
+        // rejecting table -- is queued, so that the second pass runs on full wavefronts
+        // instead of a few lanes of every wavefront.
 #pragma unroll
         for (int s = 0; s < 4; s++) {
-            res[s] = 0; j[s] = 0;
-            bool decided = L[s] == 0u;
-            if (!decided) decided = scan_chunk(lut, c0[s], L[s], 0, res[s], j[s]);
-            if (__any(!decided)) {
-                if (!decided) decided = scan_chunk(lut, c1[s], L[s], 1, res[s], j[s]);
-                if (__any(!decided)) {
-                    if (!decided) decided = scan_chunk(lut, c2[s], L[s], 2, res[s], j[s]);
-                    for (uint32_t k = 3; k < Vc.n_chunks && __any(!decided); k++)
-                        if (!decided) decided = scan_chunk(lut, Vc.chunks[(size_t)k * V + tk[s]], L[s], k, res[s], j[s]);
+            const uint32_t idx = (wave * 4u + s) * 64u + lane;
+            uint32_t res = 0, j = 0, qres = 0;
+            bool queued = false;
+            if (L[s]) {
+                if (heavy) queued = lut[(uint32_t)c0[s] & 0xFFu] != CLS_REJECT;
+                else {
+                    const bool decided = scan_chunk(lut, c0[s], L[s], 0, res, j);
+                    // (an exit on byte 7 of a longer token: the byte after it is in the next chunk)
+                    queued = !decided || (res >= 2u && j == 7u && L[s] > 8u);
+                    if (queued) { qres = decided ? res : 0u; res = 0; }
                 }
             }
-            const bool exits = res[s] >= 2u;
-            const unsigned long long bs = __ballot(res[s] == 1u);
-            const unsigned long long be = __ballot(exits && j[s] + 1u == L[s]);
-            const bool early = exits && j[s] + 1u < L[s];
-            const bool is_long = L[s] - j[s] - 1u > kShortRem;
-            bx[s] = __ballot(early && !is_long);
-            by[s] = __ballot(early && is_long);
-            stay_bits[s] = bs; end_bits[s] = be;
-            if (lane == 0) { seg[0][wave * 4u + s] = (uint32_t)__popcll(bx[s]); seg[1][wave * 4u + s] = (uint32_t)__popcll(by[s]); }
-        }
-        __syncthreads();
-        // Entries with a short remainder fill a list from the front, the others from the back, so
-        // that a wavefront of key_build walks remainders of similar length.  Every entry goes to
-        // two lists: the one of the whole class table (first V slots of the class's buffer), read
-        // by keys that are built by one workgroup, and the one of its token range (second V
-        // slots, range p owning [V + part_tok[p], V + part_tok[p+1])), read by the work items of
-        // keys that are cut by range.
-        if (threadIdx.x < 4u) {
-            const uint32_t side = threadIdx.x & 1u, which = threadIdx.x >> 1;     // which: 0 class, 1 range
-            uint32_t sum = 0;
-            for (int i = 0; i < 16; i++) { if (which == 0u) seg_pre[side][i] = sum; sum += seg[side][i]; }
-            const uint32_t ctr = which ? 2u + 2u * part + side : side;
-            seg_base[which][side] = sum ? atomicAdd(&Cc.class_count[c * kCountStride + ctr], sum) : 0u;
-        }
-        __syncthreads();
-        ExitEntry *out = Cc.class_entries[c];
-        const uint32_t out_lo = V + Vc.part_tok[part], out_hi = V + Vc.part_tok[part + 1u];
-#pragma unroll
-        for (int s = 0; s < 4; s++) {
-            const bool sh = (bx[s] >> lane) & 1ull, lg = (by[s] >> lane) & 1ull;
-            if (sh || lg) {
-                const unsigned long long mine = sh ? bx[s] : by[s];
-                const uint32_t rank = (uint32_t)__popcll(mine & ((1ull << lane) - 1ull));
-                const uint32_t nx = j[s] + 1u;           // index of the first remaining byte
-                uint32_t first;
-                if (nx < 24u) {
-                    const uint64_t cw = nx < 8u ? c0[s] : nx < 16u ? c1[s] : c2[s];
-                    first = (uint32_t)(cw >> (8u * (nx & 7u))) & 0xFFu;
-                } else first = Vc.bytes[Vc.offsets[tk[s]] + nx];
-                ExitEntry e;
-                e.tok = tk[s]; e.off = (uint8_t)nx; e.cls = (uint8_t)res[s];
-                e.first = (uint8_t)first; e.rem = (uint8_t)(L[s] - nx);
-                const uint32_t in_wg = seg_pre[sh ? 0 : 1][wave * 4u + s] + rank;
-                const uint32_t pos_c = seg_base[0][sh ? 0 : 1] + in_wg, pos_r = seg_base[1][sh ? 0 : 1] + in_wg;
-                out[sh ? pos_c : V - 1u - pos_c] = e;
-                out[sh ? out_lo + pos_r : out_hi - 1u - pos_r] = e;
+            const bool exits = res >= 2u;
+            const unsigned long long bs = __ballot(res == 1u), be = __ballot(exits && j + 1u == L[s]);
+            if (lane == 0) {
+                row_s[(wave * 4u + s) * 2u] = (uint32_t)bs; row_s[(wave * 4u + s) * 2u + 1u] = (uint32_t)(bs >> 32);
+                row_e[(wave * 4u + s) * 2u] = (uint32_t)be; row_e[(wave * 4u + s) * 2u + 1u] = (uint32_t)(be >> 32);
+            }
+            const uint32_t nxt = j + 1u;                 // index of the first remaining byte (below 8 here)
+            stage_entry(ent, n_ent, exits && nxt < L[s], tk[s], nxt, res,
+                        (uint32_t)(c0[s] >> (8u * (nxt & 7u))) & 0xFFu, L[s] - nxt);
+            const unsigned long long qm = __ballot(queued);
+            if (qm) {
+                uint32_t qb = 0;
+                if (lane == 0) qb = atomicAdd(&n_que, (uint32_t)__popcll(qm));
+                qb = __shfl(qb, 0);
+                if (queued) que[qb + (uint32_t)__popcll(qm & ((1ull << lane) - 1ull))] = idx | L[s] << 10 | qres << 18;
             }
         }
-        // The two rows of the class index, two words per wavefront slice, last: a store issued
-        // between the classification of two slices would be waited for before the next slice's
-        // operands count as loaded.
-        if (lane < 4u) {
-            unsigned long long bs = stay_bits[0], be = end_bits[0];
-#pragma unroll
-            for (uint32_t s = 1; s < 4u; s++) { bs = lane == s ? stay_bits[s] : bs; be = lane == s ? end_bits[s] : be; }
-            const uint32_t t0 = g * kScanGroup + (wave * 4u + lane) * 64u;
-            if (t0 < V) {
-                const uint32_t w0 = t0 >> 5;
-                row_stay[w0] = (uint32_t)bs; row_end[w0] = (uint32_t)be;
-                if (w0 + 1u < Vc.W) { row_stay[w0 + 1u] = (uint32_t)(bs >> 32); row_end[w0 + 1u] = (uint32_t)(be >> 32); }
+        __syncthreads();
+        // Second pass: the queued tokens, one per thread and round.
+        const uint32_t nq = n_que;
+        for (uint32_t i0 = 0; i0 < nq; i0 += 256u) {
+            const bool act = i0 + tid < nq;
+            const uint32_t q = que[act ? i0 + tid : 0u];
+            const uint32_t idx = q & 1023u, Lq = (q >> 10) & 0xFFu, qres = q >> 18;
+            const uint32_t tok = g * kScanGroup + idx;   // below V: it has bytes
+            // a rejecting table has only seen the first byte; the others know that bytes 0..7 stay
+            // (or that byte 7 exits) and go on from the second chunk
+            const uint64_t d0 = act && heavy ? Vc.chunks[tok] : 0ull;
+            const uint64_t d1 = act && Lq > 8u ? Vc.chunks[(size_t)V + tok] : 0ull;
+            const uint64_t d2 = act && Lq > 16u ? Vc.chunks[2ull * V + tok] : 0ull;
+            uint32_t res = 0, j = 0;
+            if (act) {
+                if (qres) { res = qres; j = 7u; }
+                else {
+                    bool decided = heavy ? scan_chunk(lut, d0, Lq, 0, res, j) : false;
+                    if (!decided) decided = scan_chunk(lut, d1, Lq, 1, res, j);
+                    if (!decided) decided = scan_chunk(lut, d2, Lq, 2, res, j);
+                    for (uint32_t k = 3; k < Vc.n_chunks && !decided; k++)
+                        decided = scan_chunk(lut, Vc.chunks[(size_t)k * V + tok], Lq, k, res, j);
+                }
+            }
+            const bool exits = act && res >= 2u;
+            if (act && res == 1u) atomicOr(&row_s[idx >> 5], 1u << (idx & 31u));
+            if (exits && j + 1u == Lq) atomicOr(&row_e[idx >> 5], 1u << (idx & 31u));
+            const uint32_t nxt = j + 1u;
+            const bool early = exits && nxt < Lq;
+            uint32_t first = 0;
+            if (early) {
+                if (nxt < 24u) {
+                    const uint64_t cw = nxt < 8u ? d0 : nxt < 16u ? d1 : d2;
+                    first = (uint32_t)(cw >> (8u * (nxt & 7u))) & 0xFFu;
+                } else first = Vc.bytes[Vc.offsets[tok] + nxt];
+            }
+            stage_entry(ent, n_ent, early, tok, nxt, res, first, Lq - nxt);
+        }
+        __syncthreads();
+        // Out: the workgroup's entries go to two lists, the one of the whole class table (first V
+        // slots of the class's buffer), read by keys that are built by one workgroup, and the one
+        // of its token range (second V slots, range p owning [V + part_tok[p], V + part_tok[p+1])),
+        // read by the work items of keys that are cut by range; short remainders fill a list from
+        // the front, long ones from the back, so that a wavefront of key_build walks remainders of
+        // similar length.  The four places are taken with four atomics that are in flight together.
+        const uint32_t n_short = n_ent[0], n_long = n_ent[1];
+        if (tid < 4u) {
+            const uint32_t side = tid & 1u, which = tid >> 1;              // which: 0 class, 1 range
+            const uint32_t cnt = side ? n_long : n_short;
+            const uint32_t ctr = which ? 2u + 2u * part + side : side;
+            list_base[which][side] = cnt ? atomicAdd(&Cc.class_count[c * kCountStride + ctr], cnt) : 0u;
+        }
+        __syncthreads();
+        uint2 *out = reinterpret_cast<uint2 *>(Cc.class_entries[c]);
+        const uint32_t out_lo = V + Vc.part_tok[part], out_hi = V + Vc.part_tok[part + 1u];
+        for (uint32_t i = tid; i < n_short; i += 256u) {
+            const uint2 e = ent[i];
+            out[list_base[0][0] + i] = e;
+            out[out_lo + list_base[1][0] + i] = e;
+        }
+        for (uint32_t i = tid; i < n_long; i += 256u) {
+            const uint2 e = ent[kScanGroup - 1u - i];
+            out[V - 1u - (list_base[0][1] + i)] = e;
+            out[out_hi - 1u - (list_base[1][1] + i)] = e;
+        }
+        // the three rows of the class index: all bytes stay, exit on the last byte, and their union
+        if (tid < kScanGroup / 32u) {
+            const uint32_t w = g * (kScanGroup / 32u) + tid;
+            if (w < Vc.W) {
+                uint32_t *rows = Cc.class_rows + (size_t)(3u * c) * Cc.row_stride;
+                const uint32_t a = row_s[tid], b = row_e[tid];
+                rows[w] = a; rows[Cc.row_stride + w] = b; rows[2u * Cc.row_stride + w] = a | b;
             }
         }
     }
@@ -491,8 +565,18 @@ __device__ __forceinline__ bool walk_first_hop(const DeviceTable &T, const HopSt
     return walk_chunks(T, sid, aux, c0, c1, c2, i, L);
 }
 
+// True iff the first n bytes of a token held in registers (n <= 24) all stay in the checkpoint
+// whose class table is `lut`.
+__device__ __forceinline__ bool stays_prefix(const uint8_t *lut, uint64_t c0, uint64_t c1, uint64_t c2, uint32_t n)
+{
+    for (uint32_t i = 0; i < n; i++)
+        if (lut[token_byte(c0, c1, c2, i)] != CLS_STAY) return false;
+    return true;
+}
+
 constexpr uint32_t kKbThreads = 512;       // two workgroups per compute unit
-constexpr uint32_t kKbPer = 12;            // candidates a thread filters per pass
+constexpr uint32_t kKbSegs = 2u * kMaxExitBytes;   // index ranges a key of the direct paths reads (2 for KB_SORTED)
+constexpr uint32_t kKbPer = 8;             // candidates a thread filters per pass
 constexpr uint32_t kKbQueue = kKbThreads * kKbPer;   // candidates waiting for their walk: a whole pass fits (48 KB of LDS)
 typedef __attribute__((address_space(1))) uint2 global_u2;   // a load known to go to device memory
 
@@ -517,30 +601,29 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
 {
     extern __shared__ __attribute__((aligned(16))) uint32_t row[];
     __shared__ __attribute__((aligned(16))) uint8_t hop_lut[2][256];
+    __shared__ __attribute__((aligned(16))) uint8_t own_lut[256];
     __shared__ uint2 queue[kKbQueue];
     __shared__ uint32_t queued[2];                   // candidates queued in the passes of even / odd number
-    // The first quarter of the grid serves the deep items (front of the miss list), the rest the
-    // plain ones (back), so that where a workgroup's first item lies does not depend on the counts.
-    const uint32_t deep_wgs = gridDim.x / 4u ? gridDim.x / 4u : 1u;
-    const bool serves_deep = blockIdx.x < deep_wgs || gridDim.x == 1u;
-    const bool serves_plain = blockIdx.x >= deep_wgs || gridDim.x == 1u;
+    __shared__ uint32_t seg_at[kKbSegs], seg_len[kKbSegs];   // direct paths: the index ranges of the key
+    // One sequence of work items for the whole grid: first the range items of the deep keys (front
+    // of the miss list, kParts items per key), which take longest, then the plain keys (back of the
+    // list), handed out round-robin.  Which miss entry a workgroup's first item reads is only
+    // known once the counts have arrived; it is requested beforehand as if the item were a deep
+    // one, and requested again if it turns out to be a plain one.
     const uint32_t n_deep = Cc.ctr->n_deep, n_plain = Cc.ctr->n_plain, n_claims = Cc.ctr->n_claims;
     const uint32_t rs = Cc.row_stride, tid = threadIdx.x, lane = tid & 63u;
     const bool regs_ok = Vc.lmax <= 24u;             // a whole token fits three 8-byte chunks
-    for (uint32_t list = 0; list < 2u; list++) {
-    if (list == 0u ? !serves_deep : !serves_plain) continue;
-    const uint32_t n_list = list == 0u ? n_deep * kParts : n_plain;    // a deep key is kParts work items
-    const uint32_t i_first = list == 0u || gridDim.x == 1u ? blockIdx.x : blockIdx.x - deep_wgs;
-    const uint32_t i_step = gridDim.x == 1u ? 1u : list == 0u ? deep_wgs : gridDim.x - deep_wgs;
-    // Where a workgroup's first entry lies depends on its place in the grid only, so it is
-    // requested before the counts are known (and ignored if there is no such item).
-    auto entry_of = [&](uint32_t item) {
+    const uint32_t n_deep_items = n_deep * kParts, n_items = n_deep_items + n_plain;
+    auto entry_of = [&](uint32_t list, uint32_t item) {
         const uint32_t at = list == 0u ? item / kParts : Cc.miss_cap - 1u - item;
         return at < Cc.miss_cap ? at : 0u;
     };
-    MissEntry me = Cc.miss[entry_of(i_first)];
-    for (uint32_t item = i_first; item < n_list; item += i_step) {
-        if (item != i_first) me = Cc.miss[entry_of(item)];
+    MissEntry me = Cc.miss[entry_of(0u, blockIdx.x)];
+    {
+    for (uint32_t unit = blockIdx.x; unit < n_items; unit += gridDim.x) {
+        const uint32_t list = unit < n_deep_items ? 0u : 1u;
+        const uint32_t item = list == 0u ? unit : unit - n_deep_items;
+        if (unit != blockIdx.x || list == 1u) me = Cc.miss[entry_of(list, item)];
         const uint32_t kind = me.kind, r = me.r;
         const uint32_t p0 = list == 0u ? item % kParts : 0u, span = list == 0u ? 1u : kParts;
         // this item's words of the row, in 16-byte units
@@ -552,19 +635,23 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
         const ExitEntry *ents = nullptr;
         uint32_t cnt = 0, n_front = 0, at_front = 0, at_back = 0;
         const uint4 *stay = nullptr, *end = nullptr;
-        if (kind == WG_KIND_LIT) {
+        const uint32_t mode = me.mode;
+        const bool ckpt = kind == WG_KIND_WAIT || kind == WG_KIND_COND;
+        if (kind == WG_KIND_LIT && mode == KB_LIST) {
             ents = Vc.lit_entries;
             at_front = Vc.lit_start[me.lit * kParts + p0];
             cnt = n_front = Vc.lit_start[me.lit * kParts + p0 + span] - at_front;
-        } else if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
-            ents = Cc.class_entries[me.cls];
-            const uint32_t *cc = Cc.class_count + me.cls * kCountStride + (span == kParts ? 0u : 2u + 2u * p0);
-            n_front = cc[0];
-            const uint32_t n_back = cc[1];
-            cnt = n_front + n_back;
-            at_front = span == kParts ? 0u : Vc.V + Vc.part_tok[p0];
-            at_back = (span == kParts ? Vc.V : Vc.V + Vc.part_tok[p0 + 1u]) - n_back;
-            stay = reinterpret_cast<const uint4 *>(Cc.class_rows + (size_t)(2u * me.cls) * rs);
+        } else if (ckpt) {
+            if (mode == KB_LIST) {
+                ents = Cc.class_entries[me.cls];
+                const uint32_t *cc = Cc.class_count + me.cls * kCountStride + (span == kParts ? 0u : 2u + 2u * p0);
+                n_front = cc[0];
+                const uint32_t n_back = cc[1];
+                cnt = n_front + n_back;
+                at_front = span == kParts ? 0u : Vc.V + Vc.part_tok[p0];
+                at_back = (span == kParts ? Vc.V : Vc.V + Vc.part_tok[p0 + 1u]) - n_back;
+            }
+            stay = reinterpret_cast<const uint4 *>(Cc.class_rows + (size_t)(3u * me.cls) * rs);
             end = stay + rs / 4u;
         }
         // the two possible successors: class tables staged in LDS for the first hop
@@ -573,6 +660,29 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
             if ((me.hop[w].kind == WG_KIND_WAIT || me.hop[w].kind == WG_KIND_COND) && tid < 64u)
                 reinterpret_cast<uint32_t *>(hop_lut[w])[tid] =
                     reinterpret_cast<const uint32_t *>(T.classes + (size_t)me.hop[w].cls * 256u)[tid];
+        if (mode == KB_BIGRAM && tid >= 64u && tid < 128u)
+            reinterpret_cast<uint32_t *>(own_lut)[tid - 64u] =
+                reinterpret_cast<const uint32_t *>(T.classes + (size_t)me.cls * 256u)[tid - 64u];
+        // Direct paths: the few index ranges that hold the key's candidates.  A literal state:
+        // the token that is its byte alone, and the tokens that go on with the literal byte
+        // after it (none when no byte can follow).  A checkpoint: for each exit byte e of a side
+        // whose exit leads to a literal byte y, the places in the vocabulary where y follows e.
+        uint32_t n_seg = 0;
+        if (mode == KB_SORTED) n_seg = me.hop[0].kind == WG_KIND_LIT ? 2u : 1u;
+        else if (mode == KB_BIGRAM) n_seg = (uint32_t)me.n_a + me.n_b;
+        if (tid < n_seg) {
+            const uint32_t *dir;
+            uint32_t at;
+            if (mode == KB_SORTED) { dir = Vc.dir0; at = me.lit * 257u + (tid ? 1u + me.hop[0].lit : 0u); }
+            else {
+                const uint32_t w = tid >= me.n_a, k = w ? kMaxExitBytes + tid - me.n_a : tid;
+                const uint32_t word = k < 4u ? me.exits[0] : k < 8u ? me.exits[1] : me.exits[2];
+                const uint32_t e = (word >> (8u * (k & 3u))) & 0xFFu;
+                dir = Vc.dirN; at = (e << 8) | (w ? me.hop[1].lit : me.hop[0].lit);
+            }
+            const uint32_t lo = dir[at], hi = dir[at + 1u];
+            seg_at[tid] = lo; seg_len[tid] = hi - lo;
+        }
         if (tid == 0) { queued[0] = 0; queued[1] = 0; }
         // The first pass of candidates is requested before the row is set up, so that the loads
         // are under way while (a) runs: kKbPer per thread, plain 8-byte loads from clamped
@@ -596,10 +706,8 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
         if (!stay) {
             for (uint32_t q = q_lo + tid; q < q_hi; q += kKbThreads) row4[q] = uint4{0u, 0u, 0u, 0u};
         } else if (r >= Vc.lmax) {
-            for (uint32_t q = q_lo + tid; q < q_hi; q += kKbThreads) {
-                const uint4 a = stay[q], b = end[q];
-                row4[q] = uint4{a.x | b.x, a.y | b.y, a.z | b.z, a.w | b.w};
-            }
+            const uint4 *both = end + rs / 4u;
+            for (uint32_t q = q_lo + tid; q < q_hi; q += kKbThreads) row4[q] = both[q];
         } else {
             // r allow-bytes may still be consumed: all-stay tokens need length <= r, tokens
             // that exit on their last byte have length - 1 stay bytes
@@ -617,6 +725,42 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
         // byte cannot start the literal that follows is dropped, the others wait in LDS for (b2)
         // their walk -- so that the walks, each a chain of dependent loads, run densely packed
         // instead of a few lanes of every wavefront holding the others up.
+        uint32_t examined = 0;
+        if (mode != KB_LIST) {
+            // Every candidate of a direct path is walked: a token in byte order from the key's own
+            // literal state, a byte pair from the first byte of its token -- the bytes before the
+            // pair have to stay in the checkpoint (within its byte budget), the first of the pair
+            // leaves it, and what follows is walked from the successor.
+            const global_u2 *src = (const global_u2 *)(mode == KB_SORTED ? Vc.sorted : Vc.bigram);
+            uint32_t total = 0;
+            for (uint32_t sgi = 0; sgi < n_seg; sgi++) total += seg_len[sgi];
+            for (uint32_t i = tid; i < total; i += kKbThreads) {
+                uint32_t sgi = 0, at = i;
+                while (at >= seg_len[sgi]) { at -= seg_len[sgi]; sgi++; }
+                const global_u2 *pe = src + seg_at[sgi] + at;
+                const uint32_t tok = pe->x, y = pe->y;
+                const uint32_t off = y & 0xFFu, L = off + (y >> 24);
+                const uint64_t c0 = Vc.chunks[tok];
+                const uint64_t c1 = L > 8u ? Vc.chunks[(size_t)Vc.V + tok] : 0ull;
+                const uint64_t c2 = L > 16u ? Vc.chunks[2ull * Vc.V + tok] : 0ull;
+                bool ok;
+                if (mode == KB_SORTED) {
+                    uint32_t sid = me.sid, aux = 0;
+                    ok = walk_chunks(T, sid, aux, c0, c1, c2, 0u, L);
+                } else {
+                    ok = off - 1u <= r && stays_prefix(own_lut, c0, c1, c2, off - 1u);
+                    if (ok) {
+                        const uint32_t cls = own_lut[token_byte(c0, c1, c2, off - 1u)];
+                        ok = cls >= CLS_EXIT_A &&
+                             (cls == CLS_EXIT_B ? walk_first_hop(T, me.hop[1], hop_lut[1], c0, c1, c2, off, L)
+                                                : walk_first_hop(T, me.hop[0], hop_lut[0], c0, c1, c2, off, L));
+                    }
+                }
+                if (ok) atomicOr(&row[tok >> 5], 1u << (tok & 31u));
+            }
+            examined = total;
+            __syncthreads();
+        }
         constexpr uint32_t kAnyByte = 0x100u;        // no literal follows this exit
         const uint32_t next_lit[2] = {me.hop[0].kind == WG_KIND_LIT ? me.hop[0].lit : kAnyByte,
                                       me.hop[1].kind == WG_KIND_LIT ? me.hop[1].lit : kAnyByte};
@@ -661,7 +805,7 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
             }
             __syncthreads();
         }
-        if (tid == 0) atomicAdd(&Cc.ctr->entries_walked, (unsigned long long)cnt);
+        if (tid == 0) atomicAdd(&Cc.ctr->entries_walked, (unsigned long long)cnt + examined);
         if (tid == 0 && Vc.eos_id >= 0 && me.eos_next != WG_SID_ERROR) {
             const uint32_t ew = (uint32_t)Vc.eos_id >> 5;
             if (ew >= 4u * q_lo && ew < 4u * q_hi) row[ew] |= 1u << ((uint32_t)Vc.eos_id & 31u);
@@ -1019,6 +1163,31 @@ advance_lookup_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, wg_state_t 
     lookup_one(T, Cc, env, b, live, sid, aux);
 }
 
+// The bytes a request is forced to produce next: from a state inside a Write, the rest of that
+// Write and of the Writes that follow it directly, up to the next state that is not a literal
+// byte.  One thread per request; a run of literal states is copied from the state table's
+// literal bytes.
+__global__ void __launch_bounds__(64)
+forced_bytes_kernel(DeviceTable T, const wg_state_t *__restrict__ states, uint32_t B, uint32_t cap,
+                    uint8_t *__restrict__ bytes, uint32_t *__restrict__ lens, wg_state_t *__restrict__ end_states)
+{
+    const uint32_t b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    uint32_t sid = states[b].sid, n = 0;
+    const uint32_t aux = states[b].aux;
+    uint8_t *out = bytes + (size_t)b * cap;
+    while (n < cap && sid < T.n_states) {
+        const StateDesc d = T.states[sid];
+        if ((d.kind_byte & 0xFFu) != WG_KIND_LIT) break;
+        const uint32_t m = d.run < cap - n ? d.run : cap - n;
+        for (uint32_t i = 0; i < m; i++) out[n + i] = T.lit[sid + i];
+        n += m;
+        sid = m == d.run ? d.cls : sid + m;                  // d.cls: state after the Write
+    }
+    lens[b] = n;
+    if (end_states) end_states[b] = wg_state_t{sid, n ? 0u : aux};
+}
+
 // One block per row: d_tokens[b] = index of the (draw mod popcount)-th set bit.
 __global__ void __launch_bounds__(256)
 select_kernel(const uint32_t *__restrict__ bitmask, uint32_t W, const uint64_t *__restrict__ draws,
@@ -1184,6 +1353,13 @@ hipError_t launch_advance(const DeviceTable &T, const DeviceVocab &Vc, const Dev
                           hipEvent_t *ev)
 {
     launch(advance_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s, ev, T, Vc, Cc, states, tokens, B);
+    return hipGetLastError();
+}
+
+hipError_t launch_forced_bytes(const DeviceTable &T, const wg_state_t *states, uint32_t B, uint32_t cap,
+                               uint8_t *bytes, uint32_t *lens, wg_state_t *end_states, hipStream_t s)
+{
+    forced_bytes_kernel<<<cdiv(B, 64), 64, 0, s>>>(T, states, B, cap, bytes, lens, end_states);
     return hipGetLastError();
 }
 

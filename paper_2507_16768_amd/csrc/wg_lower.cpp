@@ -241,6 +241,7 @@ class Flattener {
     uint32_t run(const Op *root) {
         uint32_t base = static_cast<uint32_t>(t_.states.size());
         uint32_t n = leaves(root);
+        n_leaves_ = n;
         end_ = base + n;
         t_.states.resize(end_ + 1);
         t_.tmpl.resize(end_ + 1, inst_);
@@ -255,11 +256,12 @@ class Flattener {
         return n ? base : end_;
     }
     uint32_t end_state() const { return end_; }
+    uint32_t num_leaves() const { return n_leaves_; }
     // states whose EOS exit must be patched once the start state is known
     const std::vector<uint32_t> &eos_exits() const { return eos_exits_; }
 
   private:
-    Table &t_; const wg_args_t *args_; uint32_t inst_; uint32_t end_ = 0;
+    Table &t_; const wg_args_t *args_; uint32_t inst_; uint32_t end_ = 0, n_leaves_ = 0;
     std::vector<uint32_t> eos_exits_;
     std::unordered_map<const Op *, uint32_t> size_memo_;
 
@@ -407,7 +409,30 @@ class Flattener {
 struct LoweringState {
     std::unordered_map<std::string, std::unique_ptr<Op>> parsed;     // static structures, by text
     std::map<std::array<uint8_t, 256>, uint32_t> class_ids;
+    // Instances seen so far by the shape of their lowered states (state ids taken relative to the
+    // instance's first state): the first state of the first instance of each shape.  A later
+    // instance of the same shape -- the same structure instantiated with the same arguments --
+    // has, state for state, the same masks, so its states share that instance's cache keys.
+    std::unordered_map<std::string, uint32_t> shapes;
 };
+
+namespace {
+// The states [first, end] of one instance as bytes that do not depend on where the instance lies
+// in the table.
+std::string shape_of(const Table &t, uint32_t first, uint32_t end) {
+    std::string out;
+    out.reserve((size_t)(end - first + 1) * 29);
+    auto rel = [&](uint32_t sid) { return sid == WG_SID_ERROR || sid == WG_SID_FINAL ? sid : sid - first + 1u; };
+    auto put = [&](uint32_t x) { out.append(reinterpret_cast<const char *>(&x), 4); };
+    for (uint32_t s = first; s <= end; s++) {
+        const StateDesc &d = t.states[s];
+        const bool lit = (d.kind_byte & 0xFFu) == WG_KIND_LIT;
+        put(d.kind_byte); put(rel(d.next_a)); put(rel(d.next_b)); put(rel(d.eos_next));
+        put(lit ? rel(d.cls) : d.cls); put(d.max); put(d.run);
+    }
+    return out;
+}
+}  // namespace
 
 Lowering::Lowering(uint32_t flags, uint32_t lmax) : st_(new LoweringState) {
     Table &t = table;
@@ -433,6 +458,7 @@ void Lowering::add(const char *const *templates, const wg_args_t *args, uint32_t
     Table &t = table;
     const size_t n_states0 = t.states.size(), n_classes0 = t.classes.size() / 256, n_start0 = t.start.size();
     const uint32_t n_keys0 = t.n_keys;
+    std::vector<std::pair<uint32_t, uint32_t>> spans;                 // first and END state of each new instance
     auto roll_back = [&]() {
         t.states.resize(n_states0); t.tmpl.resize(n_states0); t.lit.resize(n_states0);
         t.key_count.resize(n_states0); t.start.resize(n_start0); t.classes.resize(n_classes0 * 256);
@@ -459,6 +485,7 @@ void Lowering::add(const char *const *templates, const wg_args_t *args, uint32_t
             t.states[f.end_state()].eos_next = after_eos;
             for (uint32_t s : f.eos_exits()) t.states[s].eos_next = after_eos;
             t.start.push_back(start);
+            spans.emplace_back(f.end_state() - f.num_leaves(), f.end_state());
         } catch (const ParseError &e) {
             roll_back();
             throw std::runtime_error("template " + std::to_string(i) + ": " + e.what());
@@ -468,15 +495,38 @@ void Lowering::add(const char *const *templates, const wg_args_t *args, uint32_t
         }
     }
     // cache keys: one mask per state, lmax+1 for a bounded Wait (one per remaining budget
-    // 0..lmax; a larger budget cannot bind inside a single token)
+    // 0..lmax; a larger budget cannot bind inside a single token).  An instance whose lowered
+    // states equal those of an earlier instance takes that instance's keys: the global cache
+    // then serves every request of that shape from one set of rows.
     t.key_count.resize(t.states.size());
     uint32_t k = n_keys0;
-    for (size_t s = n_states0; s < t.states.size(); s++) {
-        StateDesc &d = t.states[s];
-        bool bounded = (d.kind_byte & 0xFF) == WG_KIND_WAIT && d.max != WG_UNBOUNDED;
-        t.key_count[s] = bounded ? t.lmax + 1 : 1;
-        d.key_base = k;
-        k += t.key_count[s];
+    std::vector<std::string> new_shapes;                              // to take back if memory runs out half way
+    try {
+        for (const auto &span : spans) {
+            const uint32_t first = span.first, end = span.second;
+            for (uint32_t s = first; s <= end; s++) {
+                const StateDesc &d = t.states[s];
+                const bool bounded = (d.kind_byte & 0xFF) == WG_KIND_WAIT && d.max != WG_UNBOUNDED;
+                t.key_count[s] = bounded ? t.lmax + 1 : 1;
+            }
+            std::string shape = shape_of(t, first, end);
+            const auto seen = st_->shapes.find(shape);
+            if (seen != st_->shapes.end()) {
+                const uint32_t twin = seen->second;
+                for (uint32_t s = first; s <= end; s++) t.states[s].key_base = t.states[twin + (s - first)].key_base;
+                continue;
+            }
+            new_shapes.push_back(shape);
+            st_->shapes.emplace(std::move(shape), first);
+            for (uint32_t s = first; s <= end; s++) {
+                t.states[s].key_base = k;
+                k += t.key_count[s];
+            }
+        }
+    } catch (...) {
+        for (const std::string &sh : new_shapes) st_->shapes.erase(sh);
+        roll_back();
+        throw;
     }
     t.n_keys = k;
 }

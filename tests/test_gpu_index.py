@@ -1,0 +1,276 @@
+"""GPU parity of the vocabulary indexes behind the mask build (the vocabulary in byte order with
+its two-byte prefix ranges, the byte-pair index), of the forced continuation of a Write run, and
+of the sharing of cache keys between instances of one shape -- all through the C ABI, against the
+CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+import wg_synth as ws
+from oracle import oracle as O
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2507_16768_amd as wg
+    wg.load_library()
+    return torch
+
+
+def _states_of_instances(o, n_inst):
+    """(sid, description) of every state of the first n_inst template instances."""
+    out = []
+    for sid in range(1, o.num_states):
+        d = o.describe(sid)
+        if d["tmpl"] >= n_inst:
+            break
+        out.append((sid, d))
+    return out
+
+
+@pytest.mark.parametrize("idx,n_inst", [(2, 1), (3, 1), (4, 8), (5, 16)])
+def test_every_literal_state_at_full_size(torch_cuda, idx, n_inst):
+    """Every Write-byte state of the config at its full vocabulary (config 4: of its first eight
+    instances): the mask equals the oracle's, and a state followed by another literal byte (or by
+    the end) looks at the tokens sharing its two-byte prefix only.  In these vocabularies a quarter
+    of the tokens that start with a byte are that byte alone (all of them allowed, so all of them
+    looked at); of the tokens looked at in vain, at least nine in ten are gone compared with
+    looking at every token that shares the first byte."""
+    torch = torch_cuda
+    w = ws.make_workload(idx, steps=1)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    first_byte = np.zeros(256, dtype=np.int64)
+    lens = np.diff(w.vocab.offsets.astype(np.int64))
+    has = lens > 0
+    np.add.at(first_byte, w.vocab.bytes[w.vocab.offsets[:-1][has].astype(np.int64)], 1)
+    lit = [(sid, d) for sid, d in _states_of_instances(o, n_inst) if d["kind"] == "LIT"]
+    assert len(lit) >= 10
+    # (a) the states whose successor is a literal byte or takes no byte: candidates by prefix
+    direct = [(sid, d) for sid, d in lit if o.describe(d["next"])["kind"] in ("LIT", "END")]
+    deep = [(sid, d) for sid, d in lit if o.describe(d["next"])["kind"] not in ("LIT", "END")]
+    for name, group in (("direct", direct), ("deep", deep)):
+        for lo in range(0, len(group), 256):
+            part = group[lo:lo + 256]
+            print("cfg%d %s literal states %d..%d of %d" % (idx, name, lo, lo + len(part), len(group)), flush=True)
+            st = np.array([[sid, 0] for sid, _ in part], dtype=np.uint32)
+            d_mask = torch.empty((len(st), h.W), dtype=torch.int32, device="cuda")
+            before = h.cache_stats()
+            h.fill_masks(H.dev_states(st), d_mask)
+            got = H.host_mask(d_mask)
+            after = h.cache_stats()
+            allowed = 0
+            for i, (sid, d) in enumerate(part):
+                want = o.mask_row((sid, 0))
+                assert (got[i] == want).all(), (idx, sid, d)
+                allowed += int(H.bits(want, w.vocab.V).sum())
+            assert after["builds"] - before["builds"] == len(part)
+            if name == "direct":
+                walked = after["entries_walked"] - before["entries_walked"]
+                bucket = int(sum(first_byte[d["byte"]] for _, d in part))
+                assert allowed <= walked and (walked - allowed) * 10 <= bucket - allowed, (walked, allowed, bucket)
+    assert len(direct) > 0
+
+
+@pytest.mark.parametrize("idx,n_inst", [(2, 1), (3, 1), (4, 6), (5, 16)])
+def test_every_checkpoint_state_at_full_size(torch_cuda, idx, n_inst):
+    """Every Wait / condition state (all byte budgets that bind, for a bounded Wait) at the full
+    vocabulary: whether its candidates come from the byte-pair index or from the class lists."""
+    torch = torch_cuda
+    w = ws.make_workload(idx, steps=1)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    lmax = w.vocab.lmax
+    st = []
+    for sid, d in _states_of_instances(o, n_inst):
+        if d["kind"] in ("WAIT", "COND"):
+            st.append([sid, 0])
+            if d["kind"] == "WAIT" and d["max"] >= 0:
+                st += [[sid, max(0, d["max"] - r)] for r in (0, 1, 2, 7, lmax - 1) if d["max"] - r >= 0]
+    st = np.array(st, dtype=np.uint32)
+    if idx == 5:
+        st = st[::3]                                       # (several hundred states: every third)
+    h.reserve_batch(len(st))
+    d_mask = torch.empty((len(st), h.W), dtype=torch.int32, device="cuda")
+    h.fill_masks(H.dev_states(st), d_mask)
+    got = H.host_mask(d_mask)
+    for i in range(len(st)):
+        if i % 64 == 0:
+            print("cfg%d checkpoint state %d of %d" % (idx, i, len(st)), flush=True)
+        assert (got[i] == o.mask_row((int(st[i, 0]), int(st[i, 1])))).all(), (idx, st[i], o.describe(int(st[i, 0])))
+
+
+@pytest.mark.parametrize("idx", [2, 3, 4, 5])
+def test_forced_bytes_match_the_oracle(torch_cuda, idx):
+    """wg_forced_bytes on every state of the config (plus ERROR, FINAL and out-of-range ids),
+    with a roomy cap and with one that cuts the runs: bytes, lengths and end states."""
+    torch = torch_cuda
+    w = ws.make_workload(idx, steps=1)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    sids = list(range(0, min(o.num_states, 6000))) + [O.SID_ERROR, o.num_states, o.num_states + 7]
+    st = np.array([[s, (i * 7) % 5] for i, s in enumerate(sids)], dtype=np.uint32)
+    d_states = H.dev_states(st)
+    B = len(st)
+    runs = 0
+    for cap in (64, 3, 1):
+        d_bytes = torch.full((B, cap), 0xEE, dtype=torch.uint8, device="cuda")
+        d_lens = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+        d_end = torch.full((B, 2), -1, dtype=torch.int32, device="cuda")
+        h.forced_bytes(d_states, d_bytes, d_lens, d_end)
+        gb, gl, ge = d_bytes.cpu().numpy(), d_lens.cpu().numpy(), H.host_states(d_end)
+        for i, s in enumerate(sids):
+            want, end = o.forced_bytes(s, cap)
+            assert gl[i] == len(want) and bytes(gb[i, :gl[i]]) == want, (idx, s, cap)
+            assert (gb[i, gl[i]:] == 0xEE).all()
+            assert ge[i, 0] == end and ge[i, 1] == (0 if want else st[i, 1]), (idx, s, cap)
+            runs += len(want) > 1
+        h.forced_bytes(d_states, d_bytes, d_lens)            # end states are optional
+        assert (d_lens.cpu().numpy() == gl).all()
+    assert runs > 20
+    assert (H.host_states(d_states) == st).all()             # the states are only read
+    # feeding a forced run through wg_advance, byte by byte as single-byte tokens (ids 1..256 of
+    # these vocabularies), leads to the reported end state
+    lit = [s for s in sids[:400] if s < o.num_states and o.describe(s)["kind"] == "LIT"][:64]
+    cur = np.array([[s, 0] for s in lit], dtype=np.uint32)
+    d_cur = H.dev_states(cur)
+    want = [o.forced_bytes(s, 64) for s in lit]
+    for step in range(max(len(r) for r, _ in want)):
+        tok = np.array([1 + r[step] if step < len(r) else -1 for r, _ in want], dtype=np.int32)
+        keep = H.host_states(d_cur).copy()
+        h.advance(d_cur, torch.from_numpy(np.where(tok < 0, 0, tok).astype(np.int32)).cuda())
+        now = H.host_states(d_cur).copy()
+        now[tok < 0] = keep[tok < 0]                         # (runs that have ended stay where they are)
+        d_cur.copy_(H.dev_states(now))
+    assert (H.host_states(d_cur)[:, 0] == np.array([e for _, e in want], dtype=np.uint32)).all()
+
+
+def test_instances_of_one_shape_share_their_cache_rows(torch_cuda):
+    """64 requests, each with its own instance of the same template and the same arguments: the
+    global cache builds every distinct mask once, not once per instance, and the masks and
+    states still equal the oracle's (whose instances know nothing of each other)."""
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    base = ws.make_workload(4, V=20011, B=2, steps=40)
+    texts = [base.texts[i % 2] for i in range(64)]
+    args = [base.args[i % 2] for i in range(64)]
+    import dataclasses
+    w = dataclasses.replace(base, texts=texts, args=args, B=64, request_template=np.arange(64, dtype=np.int64))
+    one = dataclasses.replace(base)                          # one instance of each of the two shapes
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    st0 = H.start_states(o, w)
+    assert (h.start_states[w.request_template] == st0).all()         # every instance keeps its own state ids
+    assert h.cache_stats()["keys"] == wg.Handle(one.texts, one.args, v).cache_stats()["keys"]
+    toks, sts, _ = o.trajectory(st0, w.token_draws(40))
+    d_states = H.dev_states(st0)
+    d_mask = torch.empty((64, h.W), dtype=torch.int32, device="cuda")
+    cur = st0
+    shapes_seen = set()
+    for k in range(40):
+        h.fill_masks(d_states, d_mask)
+        assert (H.host_mask(d_mask) == o.fill_masks(cur)).all(), k
+        for b in range(64):                                  # a mask is a function of (shape, state within it, budget)
+            first = int(st0[b, 0])
+            shapes_seen.add((b % 2, int(cur[b, 0]) - first, o.key_rem(tuple(cur[b]))))
+        h.advance(d_states, torch.from_numpy(toks[k]).cuda())
+        cur = sts[k]
+        assert (H.host_states(d_states) == cur).all(), k
+    s = h.cache_stats()
+    assert s["builds"] == len(shapes_seen) and s["builds"] < 64 * 3, (s, len(shapes_seen))
+    # a shape that joins later shares as well, a new shape gets keys of its own
+    keys = s["keys"]
+    h.add_instances(texts[:2], args[:2])
+    assert h.cache_stats()["keys"] == keys
+    other = ws.make_workload(4, V=20011, B=4, steps=1)
+    h.add_instances(other.texts[2:3], other.args[2:3])
+    assert h.cache_stats()["keys"] > keys
+
+
+def test_two_live_handles_with_long_and_short_rows(torch_cuda):
+    """A handle over the full 151,936-token vocabulary (a 19 KB row next to the builder's queue in
+    LDS) stays usable after a handle over a 4,096-token vocabulary is compiled and used in the
+    same process: fills of the two interleaved, every mask against the oracle."""
+    torch = torch_cuda
+    big = ws.make_workload(4, B=24, steps=4)
+    small = ws.make_workload(2, V=4096, B=6, steps=4)
+    ob = H.make_oracle(big)
+    vb, hb = H.make_gpu(big)
+    cur_b = H.start_states(ob, big)
+    toks_b, sts_b, _ = ob.trajectory(cur_b, big.token_draws(4))
+    os_ = H.make_oracle(small)
+    vs, hs = H.make_gpu(small)                               # compiled after the long-row handle
+    cur_s = H.start_states(os_, small)
+    toks_s, sts_s, _ = os_.trajectory(cur_s, small.token_draws(4))
+    d_b, d_s = H.dev_states(cur_b), H.dev_states(cur_s)
+    m_b = torch.empty((big.B, hb.W), dtype=torch.int32, device="cuda")
+    m_s = torch.empty((small.B, hs.W), dtype=torch.int32, device="cuda")
+    for k in range(4):
+        hs.fill_masks(d_s, m_s)
+        hb.fill_masks(d_b, m_b)
+        assert (H.host_mask(m_s) == os_.fill_masks(cur_s)).all(), k
+        assert (H.host_mask(m_b) == ob.fill_masks(cur_b)).all(), k
+        hb.advance(d_b, torch.from_numpy(toks_b[k]).cuda())
+        hs.advance(d_s, torch.from_numpy(toks_s[k]).cuda())
+        cur_b, cur_s = sts_b[k], sts_s[k]
+    assert hb.error_count() == 0 and hs.error_count() == 0
+
+
+@pytest.mark.timeout(600)
+def test_cold_steps_at_full_size_from_the_middle_of_the_trajectory(torch_cuda):
+    """The mode the benchmark times: config 4 at B=256, V=151,936, the cache cleared before every
+    fill, on ten steps taken from the middle of the oracle's trajectory: the full [256, 4748]
+    bitmask, the masked bf16 logits and the next states of every step."""
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    k_first, n = 200, 10                                  # (the oracle needs half a minute to get there)
+    w = ws.make_workload(4, steps=k_first + n)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    st0 = H.start_states(o, w)
+    toks, sts, _ = o.trajectory(st0, w.token_draws(k_first + n))
+    cur = sts[k_first - 1]
+    d_states = H.dev_states(cur)
+    d_mask = torch.empty((w.B, h.W), dtype=torch.int32, device="cuda")
+    seen = {}
+    for k in range(k_first, k_first + n):
+        print("cold step %d" % k, flush=True)
+        h.cache_clear()
+        d_mask.fill_(0x2B2B2B2B)
+        h.fill_masks(d_states, d_mask)
+        got = H.host_mask(d_mask)
+        for b in range(w.B):
+            key = (int(cur[b, 0]), int(cur[b, 1]))
+            if key not in seen:
+                seen[key] = o.mask_row(key)
+            assert (got[b] == seen[key]).all(), (k, b, key)
+        host = H.logits_for(w, tag=k)
+        d_log = H.dev_logits(host)
+        wg.apply_mask(d_log, d_mask)
+        want = O.apply_mask(host.copy(), got)
+        assert (H.host_logit_bits(d_log) == want).all(), k
+        h.advance(d_states, torch.from_numpy(toks[k]).cuda())
+        cur = sts[k]
+        assert (H.host_states(d_states) == cur).all(), k
+    s = h.cache_stats()
+    assert s["hits"] == 0 and s["lookups"] == n * w.B and h.error_count() == 0
+    # the same through the single call, again cold on every step
+    cur = sts[k_first - 1]
+    d_states = H.dev_states(sts[k_first - 2])
+    prev = torch.from_numpy(toks[k_first - 1]).cuda()
+    for k in range(k_first, k_first + 4):
+        print("cold decode_step %d" % k, flush=True)
+        h.cache_clear()
+        host = H.logits_for(w, tag=k)
+        d_log = H.dev_logits(host)
+        h.decode_step(d_states, prev, d_mask, d_log)
+        assert (H.host_states(d_states) == cur).all(), k
+        want_mask = np.stack([seen[(int(s_[0]), int(s_[1]))] for s_ in cur])
+        assert (H.host_mask(d_mask) == want_mask).all(), k
+        assert (H.host_logit_bits(d_log) == O.apply_mask(host.copy(), want_mask)).all(), k
+        prev = torch.from_numpy(toks[k]).cuda()
+        cur = sts[k]
