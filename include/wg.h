@@ -114,7 +114,8 @@ typedef struct {
     uint32_t n_keys;        /* distinct masks this state can have (budget variants) */
 } wg_state_info_t;
 
-/* ---- vocabulary ---------------------------------------------------------------------
+/* ---- vocabulary (the token map the structure factory of the section "Collaborative Parsing"
+ * is built over: every structure and every request of an engine shares one vocabulary) ------
  * CSR token bytes: token t is host_bytes[host_offsets[t] .. host_offsets[t+1]).  Both
  * arrays are host memory and are copied; eos_id < 0 means "no EOS token".  A token
  * with no bytes other than eos_id is never allowed.  The vocabulary is uploaded to
@@ -216,8 +217,10 @@ uint32_t wg_mask_words(wg_handle_t h);      /* W = ceil(V/32) */
 int wg_fill_masks(wg_handle_t h, const wg_state_t *d_states, uint32_t B, uint32_t *d_bitmask,
                   void *stream);
 
-/* wg_apply_mask: in place, logits[b][t] <- -inf (0xFF800000 / 0xFF80) where the mask bit is
- * 0; other elements keep their bit pattern.  Row b starts row_stride_elems * b elements
+/* wg_apply_mask: the mask is applied to the logits before sampling (Introduction: the binary
+ * tensor over the vocabulary, ones for allowed tokens, zeros for disallowed ones, applied to the
+ * logits prior to sampling).  In place, logits[b][t] <- -inf (0xFF800000 / 0xFF80) where the mask
+ * bit is 0; other elements keep their bit pattern.  Row b starts row_stride_elems * b elements
  * after d_logits (row_stride_elems >= V); the mask row stride is ceil(V/32) words. */
 int wg_apply_mask(void *d_logits, wg_dtype_t dtype, uint32_t B, uint32_t V,
                   int64_t row_stride_elems, const uint32_t *d_bitmask, void *stream);
@@ -270,8 +273,8 @@ int wg_masked_topk_static(const void *d_logits, wg_dtype_t dtype, uint32_t B, ui
                           int64_t row_stride_elems, const uint32_t *d_bitmask, uint32_t k,
                           int32_t *d_ids, void *d_values, void *stream);
 
-/* wg_advance: d_states[b] <- state after d_tokens[b] (state tracking, constant work per
- * symbol).  A token the state rejects, or a token id outside [0, V), gives
+/* wg_advance: d_states[b] <- state after d_tokens[b] (section "Operator Building and State
+ * Tracking": the state machine follows the output symbol by symbol, constant work per symbol).  A token the state rejects, or a token id outside [0, V), gives
  * {WG_SID_ERROR, 0} and increments the handle's device error counter. */
 int wg_advance(wg_handle_t h, wg_state_t *d_states, const int32_t *d_tokens, uint32_t B,
                void *stream);

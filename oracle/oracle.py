@@ -12,6 +12,11 @@ import numpy as np
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "wg_oracle.c")
 _LIB = os.path.join(_DIR, "libwg_oracle.so")
+# The test that plants mistakes in copies of the source points this at such a copy, to see the
+# pins fail on it; the object is then built next to the copy.
+if os.environ.get("WG_ORACLE_SOURCE"):
+    _SRC = os.path.abspath(os.environ["WG_ORACLE_SOURCE"])
+    _LIB = os.path.join(os.path.dirname(_SRC), "libwg_oracle_planted.so")
 
 SID_FINAL = 0
 SID_ERROR = 0xFFFFFFFF
