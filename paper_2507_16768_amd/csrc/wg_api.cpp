@@ -27,7 +27,8 @@ struct wg_vocab_s {
     DeviceVocab dv{};
     uint8_t *d_bytes = nullptr, *d_len8 = nullptr;
     uint32_t *d_offsets = nullptr, *d_lit_start = nullptr, *d_len_rows = nullptr;
-    uint64_t *d_chunks = nullptr;
+    uint64_t *d_chunks = nullptr, *d_sig = nullptr;
+    uint8_t *d_first8 = nullptr;
     ExitEntry *d_lit_entries = nullptr, *d_sorted = nullptr, *d_bigram = nullptr;
     uint32_t *d_dir0 = nullptr, *d_dirN = nullptr;
     int device = 0;
@@ -35,7 +36,7 @@ struct wg_vocab_s {
         (void)hipFree(d_bytes); (void)hipFree(d_len8); (void)hipFree(d_offsets);
         (void)hipFree(d_lit_start); (void)hipFree(d_len_rows); (void)hipFree(d_chunks);
         (void)hipFree(d_lit_entries); (void)hipFree(d_sorted); (void)hipFree(d_bigram);
-        (void)hipFree(d_dir0); (void)hipFree(d_dirN);
+        (void)hipFree(d_dir0); (void)hipFree(d_dirN); (void)hipFree(d_sig); (void)hipFree(d_first8);
     }
 };
 
@@ -135,15 +136,19 @@ template <class T> int regrow(T **p, size_t keep_n, size_t new_n, size_t pad_byt
 ClassInfo class_info_of(const uint8_t *table) {
     ClassInfo ci{};
     uint32_t n_a = 0, n_b = 0, live = 0;
+    unsigned long long nonstay = 0;
     for (uint32_t x = 0; x < 256; x++) {
         const uint8_t c = table[x];
         live += c != CLS_REJECT;
+        if (c != CLS_STAY) nonstay |= 1ull << (x & 63u);
         if (c == CLS_EXIT_A) { if (n_a < kMaxExitBytes) ci.a[n_a] = (uint8_t)x; n_a++; }
         if (c == CLS_EXIT_B) { if (n_b < kMaxExitBytes) ci.b[n_b] = (uint8_t)x; n_b++; }
     }
     ci.n_a = n_a > kMaxExitBytes ? kManyExits : (uint8_t)n_a;
     ci.n_b = n_b > kMaxExitBytes ? kManyExits : (uint8_t)n_b;
-    ci.flags = live <= 64 ? CI_REJECT_HEAVY : 0;
+    // (a byte-less token's signature is all ones: any mask but 0 sends it to the second pass)
+    ci.nonstay = nonstay ? nonstay : 1ull << 63;
+    ci.scan = live <= 64 ? SCAN_HEAD : __builtin_popcountll(ci.nonstay) <= 8 ? SCAN_SIG : SCAN_CHUNK;
     return ci;
 }
 
@@ -316,9 +321,18 @@ int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uin
         while (p + 1 < kParts && t >= part_tok[p + 1]) p++;
         return p;
     };
+    //  - sig / first8: one AND, or one table look-up, decides most tokens in the class scan
+    std::vector<uint64_t> sig(V, ~0ull);
+    std::vector<uint8_t> first8(V, 0);
     for (uint32_t t = 0; t < V; t++) {
         uint32_t L = ((int64_t)t == eos_id) ? 0u : off[t + 1] - off[t];
         len8[t] = (uint8_t)L;
+        if (L) {
+            uint64_t m = 0;
+            for (uint32_t i = 0; i < L; i++) m |= 1ull << (bytes[off[t] + i] & 63u);
+            sig[t] = m;
+            first8[t] = bytes[off[t]];
+        }
         for (uint32_t i = 0; i < L; i++)
             chunks[(size_t)(i / 8u) * V + t] |= (uint64_t)bytes[off[t] + i] << (8u * (i % 8u));
         if (L) {
@@ -393,6 +407,8 @@ int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uin
     if (e == hipSuccess) e = upload(&v->d_offsets, off.data(), off.size());
     if (e == hipSuccess) e = upload(&v->d_len8, len8.data(), len8.size());
     if (e == hipSuccess) e = upload(&v->d_chunks, chunks.data(), chunks.size());
+    if (e == hipSuccess) e = upload(&v->d_sig, sig.data(), sig.size());
+    if (e == hipSuccess) e = upload(&v->d_first8, first8.data(), first8.size());
     if (e == hipSuccess) e = upload(&v->d_lit_entries, lit_entries.data(), lit_entries.size());
     if (e == hipSuccess) e = upload(&v->d_lit_start, lit_start.data(), lit_start.size());
     if (e == hipSuccess) e = upload(&v->d_len_rows, len_rows.data(), len_rows.size());
@@ -405,7 +421,7 @@ int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uin
         return fail(e == hipErrorOutOfMemory ? WG_ERR_NOMEM : WG_ERR_HIP,
                     std::string("wg_vocab_create: ") + hipGetErrorString(e));
     }
-    v->dv = DeviceVocab{v->d_bytes, v->d_offsets, v->d_len8, v->d_chunks, v->d_lit_entries,
+    v->dv = DeviceVocab{v->d_bytes, v->d_offsets, v->d_len8, v->d_chunks, v->d_sig, v->d_first8, v->d_lit_entries,
                         v->d_lit_start, v->d_len_rows, v->d_sorted, v->d_dir0, v->d_bigram, v->d_dirN,
                         V, W, eos_id, lmax, n_chunks, rs, {}};
     for (uint32_t p = 0; p <= kParts; p++) v->dv.part_tok[p] = part_tok[p];

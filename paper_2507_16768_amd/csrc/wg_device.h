@@ -13,7 +13,7 @@ constexpr uint32_t kNoKey = 0xFFFFFFFFu;
 // row of a state key whose candidates all need a deep walk can be built by several workgroups,
 // each owning the words of its ranges, without any merging.
 constexpr uint32_t kParts = 8;
-constexpr uint32_t kPartGroup = 1024;
+constexpr uint32_t kPartGroup = 2048;
 
 // What the kernels want to know about a class table without reading its 256 bytes: the bytes
 // that leave through exit A / exit B (as long as there are at most kMaxExitBytes of them on a
@@ -21,11 +21,18 @@ constexpr uint32_t kPartGroup = 1024;
 constexpr uint32_t kMaxExitBytes = 6;
 struct ClassInfo {
     uint8_t n_a, n_b;            // bytes of class EXIT_A / EXIT_B, or 0xFF: more than kMaxExitBytes
-    uint8_t flags, pad;
+    uint8_t scan, pad;           // SCAN_*: how class_scan takes its first look at a token
     uint8_t a[kMaxExitBytes], b[kMaxExitBytes];
+    unsigned long long nonstay;  // SCAN_SIG: bit (x & 63) for every byte value x that does not stay (never 0)
+    unsigned long long pad2;
 };
-static_assert(sizeof(ClassInfo) == 16, "class info layout");
-enum : uint8_t { CI_REJECT_HEAVY = 1 };    // at most 64 byte values are not rejected
+static_assert(sizeof(ClassInfo) == 32, "class info layout");
+// The first look class_scan takes at a token, chosen by what the table does with most bytes:
+//   SCAN_SIG   nearly every byte value stays (a free-text Wait): a token none of whose bytes folds
+//              onto a byte value that does not stay is all-stay, by one AND with its signature;
+//   SCAN_HEAD  most byte values are rejected (an allow list): the first byte decides most tokens;
+//   SCAN_CHUNK anything between: the first 8 bytes through the table.
+enum : uint8_t { SCAN_CHUNK = 0, SCAN_SIG = 1, SCAN_HEAD = 2 };
 constexpr uint8_t kManyExits = 0xFF;
 
 struct DeviceTable {
@@ -52,6 +59,8 @@ struct DeviceVocab {
     const uint32_t *offsets;     // V + 1
     const uint8_t *len8;         // token length in bytes (0 for EOS and byte-less tokens)
     const uint64_t *chunks;      // chunks[k * V + t] = bytes 8k .. 8k+7 of token t, zero padded
+    const uint64_t *sig;         // bit (x & 63) for every byte x of the token; all ones for a byte-less token
+    const uint8_t *first8;       // the token's first byte (0 for a byte-less token)
     const ExitEntry *lit_entries;   // tokens grouped by (first byte, range): a literal state's candidates
     const uint32_t *lit_start;   // 256 * kParts + 1 bucket boundaries into lit_entries
     const uint32_t *len_rows;    // row r (0 .. lmax+1): tokens with 1 <= length <= r

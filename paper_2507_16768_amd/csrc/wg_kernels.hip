@@ -23,7 +23,7 @@
 
 namespace wg {
 
-constexpr uint32_t kScanGroup = 1024;     // tokens per class_scan workgroup
+constexpr uint32_t kScanGroup = 2048;     // tokens per class_scan workgroup
 static_assert(kScanGroup == kPartGroup, "a class_scan workgroup's tokens lie in one token range");
 static_assert(2u + 2u * kParts <= 32u, "the counters of a class fit its 128 bytes");
 constexpr uint32_t kCountStride = 32;     // class_count entries are 128 bytes apart
@@ -298,13 +298,13 @@ lookup_kernel(DeviceTable T, DeviceCache Cc, const wg_state_t *__restrict__ stat
 // class.  Results: row [stay] = tokens whose bytes all stay, row [end] = tokens that exit on
 // their last byte, and one ExitEntry per token that exits earlier.
 //
-// A workgroup handles one (class table, 1024-token group): the 256-byte table sits in LDS and
-// every lane owns 4 tokens (one in each of its wavefront's 4 slices of 64) whose lengths and
-// first 8-byte chunks are requested before the table is known.  A first pass decides what the
-// first chunk can decide (for a table that rejects most byte values: what the first byte can
-// decide); the tokens that need more are queued in LDS and finished by a second pass on full
-// wavefronts.  Rows and exit entries are assembled in LDS and leave in whole runs; the places
-// of the entries in the global lists are taken with four atomics per workgroup.
+// A workgroup handles one (class table, 2048-token group): the 256-byte table sits in LDS and
+// every lane owns 8 tokens (one in each of its wavefront's 8 slices of 64).  A first look
+// settles most tokens with one instruction or one table look-up each (which one depends on the
+// table: all bytes stay by the token's byte signature, rejected by the first byte, or the first
+// 8 bytes through the table); the rest are queued in LDS and finished byte by byte on full
+// wavefronts.  Rows and exit entries are assembled in LDS and leave in whole runs; the places of
+// the entries in the global lists are taken with four atomics per workgroup.
 
 // Classifies up to 8 bytes of one chunk.  Returns true once the token is decided.
 __device__ __forceinline__ bool scan_chunk(const uint8_t *lut, uint64_t cb, uint32_t L, uint32_t k,
@@ -352,13 +352,17 @@ __device__ __forceinline__ void stage_entry(uint2 *ent, uint32_t *n_ent, bool ea
     }
 }
 
-__global__ void __launch_bounds__(256)
+constexpr uint32_t kScanThreads = 256;
+constexpr uint32_t kScanPer = kScanGroup / kScanThreads;     // tokens per lane of class_scan
+static_assert(kScanPer * kScanThreads == kScanGroup, "a lane owns a whole number of tokens");
+
+__global__ void __launch_bounds__(kScanThreads) __attribute__((amdgpu_waves_per_eu(5, 8)))
 class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
 {
     __shared__ __attribute__((aligned(16))) uint8_t lut[256];
     __shared__ uint32_t row_s[kScanGroup / 32u], row_e[kScanGroup / 32u];   // the group's words of the two rows
     __shared__ uint2 ent[kScanGroup];                // early exits of the group, from both ends
-    __shared__ uint32_t que[kScanGroup];             // tokens the first pass could not decide
+    __shared__ uint16_t que[kScanGroup];             // tokens (by their place in the group) the first look did not decide
     __shared__ uint32_t n_ent[2], n_que;
     __shared__ uint32_t list_base[2][2];             // where this workgroup's entries start in the two lists
     const uint32_t n = Cc.ctr->n_class_miss;
@@ -381,17 +385,17 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
     for (uint64_t item = local; item < total; item += local_wgs) {
         const uint32_t ci = (uint32_t)(item / my_groups);
         const uint32_t g = (uint32_t)(item % my_groups) * nx + xcd;
-        // The tokens do not depend on the table: their lengths and first chunks are requested
-        // before the table is known.  A lane owns 4 tokens, one in each of its wavefront's 4
-        // slices of 64, so that a ballot over a slice is two words of a row.
-        uint32_t tk[4], L[4];
-        uint64_t c0[4];
+        // What the first look needs of a token does not depend on the table: the signatures and
+        // first bytes of the lane's tokens are requested before the table is known.  A lane owns
+        // kScanPer tokens, one in each of its wavefront's slices of 64, so that a ballot over a
+        // slice is two words of a row.
+        unsigned long long sg[kScanPer];
+        uint32_t fb[kScanPer];
 #pragma unroll
-        for (int s = 0; s < 4; s++) {
-            tk[s] = g * kScanGroup + (wave * 4u + s) * 64u + lane;
-            const bool valid = tk[s] < V;
-            L[s] = valid ? Vc.len8[tk[s]] : 0u;
-            c0[s] = valid ? Vc.chunks[tk[s]] : 0ull;
+        for (uint32_t s = 0; s < kScanPer; s++) {
+            const uint32_t tk = g * kScanGroup + (wave * kScanPer + s) * 64u + lane;
+            sg[s] = tk < V ? Vc.sig[tk] : 0ull;
+            fb[s] = tk < V ? Vc.first8[tk] : 0u;
         }
         const uint32_t c = item == local ? c_first : Cc.class_miss[ci];
         uint32_t part = 0;
@@ -400,72 +404,80 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
         __syncthreads();                             // the item before is done with the LDS
         if (tid < 64u)
             reinterpret_cast<uint32_t *>(lut)[tid] = reinterpret_cast<const uint32_t *>(T.classes + (size_t)c * 256u)[tid];
+        if (tid < kScanGroup / 32u) row_e[tid] = 0;
         if (tid == 0) { n_ent[0] = 0; n_ent[1] = 0; n_que = 0; }
-        // A table that rejects most byte values decides most tokens by their first byte: the
-        // first pass looks at that byte only.
-        const bool heavy = (T.class_info[c].flags & CI_REJECT_HEAVY) != 0;
+        const uint32_t scan = T.class_info[c].scan;
+        const unsigned long long nonstay = T.class_info[c].nonstay;
         __syncthreads();
-        // First pass, every token: its first 8 bytes (its first byte, for a rejecting table).
-        // A token that needs more -- bytes beyond the first chunk, or any further look for a
-        // rejecting table -- is queued, so that the second pass runs on full wavefronts
-        // instead of a few lanes of every wavefront.
+        // First look, every token.  It settles the tokens whose bytes all stay (a table where
+        // nearly every byte value stays: none of the token's bytes folds onto one that does not),
+        // the tokens rejected by their first byte (a table that rejects most byte values), or what
+        // the first 8 bytes settle without leaving an exit entry; every other token is queued,
+        // so that the byte-by-byte work runs on full wavefronts.
+        unsigned long long qm[kScanPer];             // per slice: the lanes whose token is queued
+        uint32_t n_mine = 0;                         // queued tokens of this wavefront
 #pragma unroll
-        for (int s = 0; s < 4; s++) {
-            const uint32_t idx = (wave * 4u + s) * 64u + lane;
-            uint32_t res = 0, j = 0, qres = 0;
-            bool queued = false;
-            if (L[s]) {
-                if (heavy) queued = lut[(uint32_t)c0[s] & 0xFFu] != CLS_REJECT;
-                else {
-                    const bool decided = scan_chunk(lut, c0[s], L[s], 0, res, j);
-                    // (an exit on byte 7 of a longer token: the byte after it is in the next chunk)
-                    queued = !decided || (res >= 2u && j == 7u && L[s] > 8u);
-                    if (queued) { qres = decided ? res : 0u; res = 0; }
-                }
+        for (uint32_t s = 0; s < kScanPer; s++) {
+            const uint32_t tk = g * kScanGroup + (wave * kScanPer + s) * 64u + lane;
+            const bool valid = tk < V;
+            bool stays = false, ends = false, queued = false;
+            if (scan == SCAN_SIG) {
+                queued = valid && (sg[s] & nonstay) != 0ull;
+                stays = valid && !queued;
+            } else if (scan == SCAN_HEAD) {
+                queued = valid && lut[fb[s]] != CLS_REJECT;
+            } else if (valid) {
+                const uint32_t L = Vc.len8[tk];
+                uint32_t res = 0, j = 0;
+                const bool decided = L == 0u || scan_chunk(lut, Vc.chunks[tk], L, 0, res, j);
+                stays = decided && res == 1u;
+                ends = decided && res >= 2u && j + 1u == L;
+                queued = !decided || (res >= 2u && j + 1u < L);
             }
-            const bool exits = res >= 2u;
-            const unsigned long long bs = __ballot(res == 1u), be = __ballot(exits && j + 1u == L[s]);
+            const unsigned long long bs = __ballot(stays), be = __ballot(ends);
             if (lane == 0) {
-                row_s[(wave * 4u + s) * 2u] = (uint32_t)bs; row_s[(wave * 4u + s) * 2u + 1u] = (uint32_t)(bs >> 32);
-                row_e[(wave * 4u + s) * 2u] = (uint32_t)be; row_e[(wave * 4u + s) * 2u + 1u] = (uint32_t)(be >> 32);
+                row_s[(wave * kScanPer + s) * 2u] = (uint32_t)bs; row_s[(wave * kScanPer + s) * 2u + 1u] = (uint32_t)(bs >> 32);
+                if (be) { row_e[(wave * kScanPer + s) * 2u] = (uint32_t)be; row_e[(wave * kScanPer + s) * 2u + 1u] = (uint32_t)(be >> 32); }
             }
-            const uint32_t nxt = j + 1u;                 // index of the first remaining byte (below 8 here)
-            stage_entry(ent, n_ent, exits && nxt < L[s], tk[s], nxt, res,
-                        (uint32_t)(c0[s] >> (8u * (nxt & 7u))) & 0xFFu, L[s] - nxt);
-            const unsigned long long qm = __ballot(queued);
-            if (qm) {
-                uint32_t qb = 0;
-                if (lane == 0) qb = atomicAdd(&n_que, (uint32_t)__popcll(qm));
-                qb = __shfl(qb, 0);
-                if (queued) que[qb + (uint32_t)__popcll(qm & ((1ull << lane) - 1ull))] = idx | L[s] << 10 | qres << 18;
+            qm[s] = __ballot(queued);
+            n_mine += (uint32_t)__popcll(qm[s]);
+        }
+        {
+            // the wavefront's queued tokens take their places together: one LDS atomic, then a
+            // token's place is the wavefront's first place, plus the queued tokens of the slices
+            // before, plus the queued lanes below in its own slice
+            uint32_t qb = 0;
+            if (lane == 0 && n_mine) qb = atomicAdd(&n_que, n_mine);
+            qb = __shfl(qb, 0);
+#pragma unroll
+            for (uint32_t s = 0; s < kScanPer; s++) {
+                if ((qm[s] >> lane) & 1ull)
+                    que[qb + (uint32_t)__popcll(qm[s] & ((1ull << lane) - 1ull))] = (uint16_t)((wave * kScanPer + s) * 64u + lane);
+                qb += (uint32_t)__popcll(qm[s]);
             }
         }
         __syncthreads();
-        // Second pass: the queued tokens, one per thread and round.
+        // Second look: the queued tokens byte by byte, one per thread and round.
         const uint32_t nq = n_que;
-        for (uint32_t i0 = 0; i0 < nq; i0 += 256u) {
+        for (uint32_t i0 = 0; i0 < nq; i0 += kScanThreads) {
             const bool act = i0 + tid < nq;
-            const uint32_t q = que[act ? i0 + tid : 0u];
-            const uint32_t idx = q & 1023u, Lq = (q >> 10) & 0xFFu, qres = q >> 18;
-            const uint32_t tok = g * kScanGroup + idx;   // below V: it has bytes
-            // a rejecting table has only seen the first byte; the others know that bytes 0..7 stay
-            // (or that byte 7 exits) and go on from the second chunk
-            const uint64_t d0 = act && heavy ? Vc.chunks[tok] : 0ull;
-            const uint64_t d1 = act && Lq > 8u ? Vc.chunks[(size_t)V + tok] : 0ull;
-            const uint64_t d2 = act && Lq > 16u ? Vc.chunks[2ull * V + tok] : 0ull;
+            const uint32_t idx = que[act ? i0 + tid : 0u];
+            const uint32_t tok = g * kScanGroup + idx;           // below V
+            const uint32_t Lq = act ? Vc.len8[tok] : 0u;
+            // (all three chunks are requested at once, whatever the length: no load waits for another)
+            const uint64_t d0 = Vc.chunks[tok];
+            const uint64_t d1 = Vc.chunks[(Vc.n_chunks > 1u ? (size_t)V : 0u) + tok];
+            const uint64_t d2 = Vc.chunks[(Vc.n_chunks > 2u ? 2ull * V : 0ull) + tok];
             uint32_t res = 0, j = 0;
-            if (act) {
-                if (qres) { res = qres; j = 7u; }
-                else {
-                    bool decided = heavy ? scan_chunk(lut, d0, Lq, 0, res, j) : false;
-                    if (!decided) decided = scan_chunk(lut, d1, Lq, 1, res, j);
-                    if (!decided) decided = scan_chunk(lut, d2, Lq, 2, res, j);
-                    for (uint32_t k = 3; k < Vc.n_chunks && !decided; k++)
-                        decided = scan_chunk(lut, Vc.chunks[(size_t)k * V + tok], Lq, k, res, j);
-                }
+            if (Lq) {
+                bool decided = scan_chunk(lut, d0, Lq, 0, res, j);
+                if (!decided) decided = scan_chunk(lut, d1, Lq, 1, res, j);
+                if (!decided) decided = scan_chunk(lut, d2, Lq, 2, res, j);
+                for (uint32_t k = 3; k < Vc.n_chunks && !decided; k++)
+                    decided = scan_chunk(lut, Vc.chunks[(size_t)k * V + tok], Lq, k, res, j);
             }
-            const bool exits = act && res >= 2u;
-            if (act && res == 1u) atomicOr(&row_s[idx >> 5], 1u << (idx & 31u));
+            const bool exits = res >= 2u;
+            if (res == 1u) atomicOr(&row_s[idx >> 5], 1u << (idx & 31u));
             if (exits && j + 1u == Lq) atomicOr(&row_e[idx >> 5], 1u << (idx & 31u));
             const uint32_t nxt = j + 1u;
             const bool early = exits && nxt < Lq;
@@ -495,12 +507,12 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
         __syncthreads();
         uint2 *out = reinterpret_cast<uint2 *>(Cc.class_entries[c]);
         const uint32_t out_lo = V + Vc.part_tok[part], out_hi = V + Vc.part_tok[part + 1u];
-        for (uint32_t i = tid; i < n_short; i += 256u) {
+        for (uint32_t i = tid; i < n_short; i += kScanThreads) {
             const uint2 e = ent[i];
             out[list_base[0][0] + i] = e;
             out[out_lo + list_base[1][0] + i] = e;
         }
-        for (uint32_t i = tid; i < n_long; i += 256u) {
+        for (uint32_t i = tid; i < n_long; i += kScanThreads) {
             const uint2 e = ent[kScanGroup - 1u - i];
             out[V - 1u - (list_base[0][1] + i)] = e;
             out[out_hi - 1u - (list_base[1][1] + i)] = e;
@@ -577,17 +589,18 @@ __device__ __forceinline__ bool stays_prefix(const uint8_t *lut, uint64_t c0, ui
 constexpr uint32_t kKbThreads = 512;       // two workgroups per compute unit
 constexpr uint32_t kKbSegs = 2u * kMaxExitBytes;   // index ranges a key of the direct paths reads (2 for KB_SORTED)
 constexpr uint32_t kKbPer = 8;             // candidates a thread filters per pass
+static_assert(kKbPer % 2u == 0u, "deep items take their candidates two at a time");
 constexpr uint32_t kKbQueue = kKbThreads * kKbPer;   // candidates waiting for their walk: a whole pass fits (48 KB of LDS)
 typedef __attribute__((address_space(1))) uint2 global_u2;   // a load known to go to device memory
 
 // Walks what is left of a candidate token from the state its exit leads to.
 __device__ __forceinline__ bool walk_candidate(const DeviceTable &T, const DeviceVocab &Vc, const MissEntry &me,
-                                               const uint8_t (*hop_lut)[256], const ExitEntry &x, bool regs_ok)
+                                               const uint8_t (*hop_lut)[256], const ExitEntry &x, bool regs_ok,
+                                               uint64_t c0)
 {
     const int w = x.cls == CLS_EXIT_B;
     if (regs_ok) {
         const uint32_t L = (uint32_t)x.off + x.rem;
-        const uint64_t c0 = Vc.chunks[x.tok];
         const uint64_t c1 = L > 8u ? Vc.chunks[(size_t)Vc.V + x.tok] : 0ull;
         const uint64_t c2 = L > 16u ? Vc.chunks[2ull * Vc.V + x.tok] : 0ull;
         return walk_first_hop(T, me.hop[w], hop_lut[w], c0, c1, c2, x.off, L);
@@ -761,6 +774,36 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
             examined = total;
             __syncthreads();
         }
+        if (mode == KB_LIST && list == 0u) {
+            // A range item of a deep key: every entry of its list that is within the byte budget
+            // has to be walked (the successor is a checkpoint, so no first byte rules an entry
+            // out), which leaves nothing to filter: each thread walks the entries it requested.
+            for (uint32_t i0 = 0; i0 < cnt; i0 += kKbThreads * kKbPer) {
+                if (i0) request(i0);
+                // two candidates at a time, their first chunks requested together (most tokens
+                // are no longer than that), so that the two walks do not queue up behind one
+                // another's first load
+#pragma unroll
+                for (uint32_t j = 0; j < kKbPer; j += 2u) {
+                    if (i0 + j * kKbThreads >= cnt) break;    // no candidate left for any thread
+                    uint64_t first_chunk[2];
+#pragma unroll
+                    for (uint32_t u = 0; u < 2u; u++) first_chunk[u] = Vc.chunks[x[j + u].x < Vc.V ? x[j + u].x : 0u];
+#pragma unroll
+                    for (uint32_t u = 0; u < 2u; u++) {
+                        ExitEntry e;
+                        e.tok = x[j + u].x; e.off = (uint8_t)x[j + u].y; e.cls = (uint8_t)(x[j + u].y >> 8);
+                        e.first = (uint8_t)(x[j + u].y >> 16); e.rem = (uint8_t)(x[j + u].y >> 24);
+                        if (i0 + (j + u) * kKbThreads + tid < cnt && (uint32_t)e.off - 1u <= r &&
+                            (e.rem == 0 || walk_candidate(T, Vc, me, hop_lut, e, regs_ok, first_chunk[u])))
+                            atomicOr(&row[e.tok >> 5], 1u << (e.tok & 31u));
+                    }
+                }
+            }
+            examined = cnt;
+            cnt = 0;                                     // nothing left for the filter below
+            __syncthreads();
+        }
         constexpr uint32_t kAnyByte = 0x100u;        // no literal follows this exit
         const uint32_t next_lit[2] = {me.hop[0].kind == WG_KIND_LIT ? me.hop[0].lit : kAnyByte,
                                       me.hop[1].kind == WG_KIND_LIT ? me.hop[1].lit : kAnyByte};
@@ -801,7 +844,7 @@ key_build_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc, uint32_t *__rest
                 const uint2 q = queue[i];
                 ExitEntry e;
                 e.tok = q.x; e.off = (uint8_t)q.y; e.cls = (uint8_t)(q.y >> 8); e.first = (uint8_t)(q.y >> 16); e.rem = (uint8_t)(q.y >> 24);
-                if (walk_candidate(T, Vc, me, hop_lut, e, regs_ok)) atomicOr(&row[e.tok >> 5], 1u << (e.tok & 31u));
+                if (walk_candidate(T, Vc, me, hop_lut, e, regs_ok, Vc.chunks[e.tok])) atomicOr(&row[e.tok >> 5], 1u << (e.tok & 31u));
             }
             __syncthreads();
         }
@@ -1281,7 +1324,7 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
     uint32_t groups = cdiv(Vc.V, kScanGroup);
     uint64_t scan_items = (uint64_t)B * groups;
     uint32_t cap = n_cu * 8u;
-    launch(class_scan_kernel, dim3(scan_items < cap ? (uint32_t)scan_items : cap), dim3(256), 0, s,
+    launch(class_scan_kernel, dim3(scan_items < cap ? (uint32_t)scan_items : cap), dim3(kScanThreads), 0, s,
            ev ? ev + 2 : nullptr, T, Vc, Cc);
     // up to kParts work items per key; two 512-thread workgroups fit a compute unit
     const uint32_t kb = n_cu * 2u;
