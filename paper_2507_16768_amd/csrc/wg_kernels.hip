@@ -223,12 +223,24 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceCac
             deep = ((kind == WG_KIND_LIT || kind == WG_KIND_WAIT) && ckpt0) || (kind == WG_KIND_COND && (ckpt0 || ckpt1));
         }
         const unsigned long long dm = __ballot(claimed && deep), pm = cm & ~dm;
-        // three counters, three lanes: the atomics are in flight together
+        // The claim of the class table goes out first, so that its compare-and-swap is in flight
+        // together with the three counters of the key claims (three counters, three lanes).
+        const bool ckpt = kind == WG_KIND_WAIT || kind == WG_KIND_COND;
+        const bool want_class = claimed && ckpt && class_gen != epoch;
+        uint32_t class_was = epoch;
+        if (want_class) class_was = atomicCAS(&Cc.class_built[d.cls], class_gen, epoch);
         uint32_t got = 0;
         if (lane == 0) got = atomicAdd(&Cc.ctr->n_claims, (uint32_t)__popcll(cm));
         else if (lane == 1 && dm) got = atomicAdd(&Cc.ctr->n_deep, (uint32_t)__popcll(dm));
         else if (lane == 2 && pm) got = atomicAdd(&Cc.ctr->n_plain, (uint32_t)__popcll(pm));
         const uint32_t first_key = __shfl(got, 0), first_deep = __shfl(got, 1), first_plain = __shfl(got, 2);
+        const bool class_claimed = want_class && class_was == class_gen;
+        const unsigned long long ccm = __ballot(class_claimed);
+        uint32_t first_class = 0;
+        if (ccm) {
+            if (lane == 0) first_class = atomicAdd(&Cc.ctr->n_class_miss, (uint32_t)__popcll(ccm));
+            first_class = __shfl(first_class, 0);
+        }
         if (claimed) {
             const unsigned long long below = (1ull << lane) - 1ull;
             const uint32_t idx = first_key + (uint32_t)__popcll(cm & below);
@@ -249,8 +261,7 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceCac
             if (!deep && T.lmax <= 24u) {
                 const bool lit0 = hop[0].kind == WG_KIND_LIT, lit1 = hop[1].kind == WG_KIND_LIT;
                 if (kind == WG_KIND_LIT) me.mode = KB_SORTED;
-                else if ((kind == WG_KIND_WAIT || kind == WG_KIND_COND) &&
-                         (!lit0 || ci.n_a != kManyExits) && (!lit1 || ci.n_b != kManyExits)) {
+                else if (ckpt && (!lit0 || ci.n_a != kManyExits) && (!lit1 || ci.n_b != kManyExits)) {
                     me.mode = KB_BIGRAM;
                     me.n_a = lit0 ? ci.n_a : 0; me.n_b = lit1 ? ci.n_b : 0;
                     me.exits[0] = ci.a[0] | ci.a[1] << 8 | ci.a[2] << 16 | (uint32_t)ci.a[3] << 24;
@@ -260,16 +271,13 @@ __device__ __forceinline__ void lookup_one(const DeviceTable &T, const DeviceCac
             }
             Cc.miss[deep ? first_deep + (uint32_t)__popcll(dm & below)
                          : Cc.miss_cap - 1u - (first_plain + (uint32_t)__popcll(pm & below))] = me;
-            if (kind == WG_KIND_WAIT || kind == WG_KIND_COND) {
+            if (class_claimed) {
+                // the class list and the list of each token range: short entries fill from the
+                // front, long ones from the back
                 const uint32_t c = d.cls;
-                const uint32_t oc = class_gen;
-                if (oc != epoch && atomicCAS(&Cc.class_built[c], oc, epoch) == oc) {
-                    // the class list and the list of each token range: short entries fill from the
-                    // front, long ones from the back
 #pragma unroll
-                    for (uint32_t i = 0; i < 2u + 2u * kParts; i++) Cc.class_count[c * kCountStride + i] = 0;
-                    Cc.class_miss[atomicAdd(&Cc.ctr->n_class_miss, 1u)] = c;
-                }
+                for (uint32_t i = 0; i < 2u + 2u * kParts; i++) Cc.class_count[c * kCountStride + i] = 0;
+                Cc.class_miss[first_class + (uint32_t)__popcll(ccm & below)] = c;
             }
         }
     }
