@@ -30,15 +30,19 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch in the cold steps of this workload, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE (profiles/bench_config4_hbm_traffic.txt; fetch scaled x2.000, write x1.000 by
-# the counters of a 512 MiB device copy).  They describe the kernels whose source hashes to
-# TRAFFIC_SOURCE_SHA256; with any other kernel source the field is reported as null.
-TRAFFIC_BYTES = {"class_scan": 4.09e6, "key_build": 13.99e6, "gather": 0.04e6, "apply": 57.70e6}
+# HBM bytes per launch in the cold steps of workloads 4 and 5, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE (profiles/bench_config4_hbm_traffic.txt, profiles/bench_config5_hbm_traffic.txt; fetch
+# scaled x2.000, write x1.000 by the counters of a 512 MiB device copy).  They describe the kernels
+# whose source hashes to TRAFFIC_SOURCE_SHA256; with any other kernel source, or any other workload,
+# the field is reported as null.
+TRAFFIC_BYTES = {
+    4: {"lookup": 0.16e6, "class_scan": 6.28e6, "key_build": 15.60e6, "gather": 0.04e6, "apply": 57.08e6, "advance": 0.21e6},
+    5: {"lookup": 0.42e6, "class_scan": 23.51e6, "key_build": 34.17e6, "gather": 14.15e6, "apply": 314.63e6, "advance": 0.75e6},
+}
+TRAFFIC_SOURCE_SHA256 = "02f32eed57ab1830334b69eef30fb23fd0cbd7dd88ab1daed20fc7273d4f3898"
 WINDOW_START = 64              # first timed step of the trajectory (the warm-up steps come right before it)
 N_PASSES = 5                   # timed passes per figure; the median is reported
 RAMP_SECONDS = 0.08            # GPU work done before timing, for the clocks to settle
-TRAFFIC_SOURCE_SHA256 = "70e63cf2bd68caa2bce1230b891b3e50fa1ca58b792890c22e0d07cab9d494f8"
 
 
 def kernel_source_sha256():
@@ -608,7 +612,7 @@ def main():
         gbs = nbytes / (us * 1e-6) / 1e9 if us > 0 else 0.0
         kernels.append({"kernel": name, "algorithmic_bytes_per_launch": nbytes, "us_per_launch": us,
                         "achieved_GBs": gbs, "frac": gbs / HBM_PEAK_GBS,
-                        "traffic": TRAFFIC_BYTES.get(name) if traffic_ok else None,
+                        "traffic": TRAFFIC_BYTES.get(w.index, {}).get(name) if traffic_ok else None,
                         "bound": "hbm" if name in ("class_scan", "key_build", "gather", "apply") else "latency"})
     dominant = max((k for k in kernels if k["bound"] == "hbm"), key=lambda k: k["us_per_launch"])
     method_bytes_cold = sum(v[0] for v in alg.values())
