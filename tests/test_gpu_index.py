@@ -274,3 +274,56 @@ def test_cold_steps_at_full_size_from_the_middle_of_the_trajectory(torch_cuda):
         assert (H.host_logit_bits(d_log) == O.apply_mask(host.copy(), want_mask)).all(), k
         prev = torch.from_numpy(toks[k]).cuda()
         cur = sts[k]
+
+
+def test_every_kind_of_class_table_and_candidate_source(torch_cuda):
+    """Checkpoints chosen so that every first look of the class scan and every candidate source of
+    the row build is taken: printable text up to '<' (neither nearly-all-stay nor mostly-reject),
+    a free-text Wait, allow lists; exits of one, six, seven and ten byte values in front of a
+    literal (up to six are looked up by byte pair, more take the class list), in front of the end,
+    and in front of another checkpoint; with and without byte budgets.  Every state and budget
+    against the oracle on a 20,011-token vocabulary, cold and again warm."""
+    torch = torch_cuda
+    base = ws.make_workload(2, V=20011, B=1, steps=1)
+    texts = [
+        r'Sequence(Wait(allow={[\x20-\x7e]}, wait={<}), Write("/p>"), Wait(allow={[\x20-\x7e]}, wait={<}, max=9), Write("a"))',
+        r'Sequence(Wait(allow={\w}, wait={\d}), Write("ab"), Wait(allow={\w, \s, \., -}, wait={\d}, max=5), Write("0"))',
+        r'Sequence(Wait(denies={}, wait={a, b, c, d, e, f}), Write("gh"), Wait(denies={\n}, wait={a, b, c, d, e, f, g}), Write("hi"))',
+        r'Sequence(Wait(allow={[a-z]}, wait={\d}), Wait(denies={}, wait={[0-4]}, max=12), Wait(allow={\d}, wait={;}))',
+        r'IfElse(condition=Wait(allow={\ }, true_waits={[0-6]}, false_waits={[a-f]}), if_body=Write("x1"), else_body=None)',
+        r'DoWhile(body=Sequence(Write("k"), Wait(allow={[\x20-\x7e]}, wait={\", \x27})), '
+        r'condition=Wait(allow={\s}, true_waits={\,, ;}, false_waits={\., !, ?}))',
+        r'Sequence(Write("q"), Wait(allow={[\x00-\xff]}, wait={<eos>}))',
+    ]
+    import dataclasses
+    w = dataclasses.replace(base, texts=texts, args=[{}] * len(texts), B=len(texts),
+                            request_template=np.arange(len(texts), dtype=np.int64))
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    lmax = w.vocab.lmax
+    st = []
+    for sid in range(1, o.num_states):
+        d = o.describe(sid)
+        st.append([sid, 0])
+        if d["kind"] == "WAIT" and d["max"] >= 0:
+            st += [[sid, a] for a in range(1, d["max"] + 2)]
+    st = np.array(st, dtype=np.uint32)
+    want = o.fill_masks(st)
+    d_mask = torch.empty((len(st), h.W), dtype=torch.int32, device="cuda")
+    for rep in ("cold", "warm"):
+        d_mask.fill_(0x66666666)
+        h.fill_masks(H.dev_states(st), d_mask)
+        got = H.host_mask(d_mask)
+        bad = np.nonzero((got != want).any(axis=1))[0]
+        assert len(bad) == 0, (rep, st[bad[0]], o.describe(int(st[bad[0], 0])))
+    s = h.cache_stats()
+    assert s["class_scans"] >= 10 and s["hits"] == len(st)
+    # and the advance of every token from the start state of each template
+    V = w.vocab.V
+    for t in range(len(texts)):
+        s0 = o.start_state(t)
+        rep_states = np.tile(np.array([[s0, 0]], dtype=np.uint32), (V, 1))
+        tk = np.arange(V, dtype=np.int32)
+        d_st = H.dev_states(rep_states)
+        h.advance(d_st, torch.from_numpy(tk).cuda())
+        assert (H.host_states(d_st) == o.advance(rep_states, tk)).all(), t
