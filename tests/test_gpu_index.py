@@ -327,3 +327,55 @@ def test_every_kind_of_class_table_and_candidate_source(torch_cuda):
         d_st = H.dev_states(rep_states)
         h.advance(d_st, torch.from_numpy(tk).cuda())
         assert (H.host_states(d_st) == o.advance(rep_states, tk)).all(), t
+
+
+@pytest.mark.timeout(600)
+def test_the_largest_batch_one_call_takes(torch_cuda):
+    """B = 65,535 requests in one call (the most a call takes; one more is refused): masks, masked
+    fp32 logits and next states of every request, the requests spread over every state of a
+    config-3 instance on a 1,003-token vocabulary."""
+    torch = torch_cuda
+    import paper_2507_16768_amd as wg
+    B = 65535
+    w = ws.make_workload(3, V=1003, B=4, steps=1)
+    o = H.make_oracle(w)
+    v, h = H.make_gpu(w)
+    with pytest.raises(wg.WgError):
+        h.reserve_batch(B + 1)
+    h.reserve_batch(B)
+    distinct = []
+    for sid in range(0, o.num_states):
+        d = o.describe(sid)
+        distinct.append((sid, 0))
+        if d["kind"] == "WAIT" and d["max"] >= 0:
+            distinct += [(sid, d["max"] - r) for r in range(0, 12) if d["max"] - r > 0]
+    distinct.append((O.SID_ERROR, 0))
+    rows = np.stack([o.mask_row(s) for s in distinct])
+    pick = (np.arange(B) * 7919) % len(distinct)
+    st = np.array([distinct[i] for i in pick], dtype=np.uint32)
+    d_states = H.dev_states(st)
+    d_mask = torch.full((B, h.W), 0x0F0F0F0F, dtype=torch.int32, device="cuda")
+    h.fill_masks(d_states, d_mask)
+    assert (H.host_mask(d_mask) == rows[pick]).all()
+    s = h.cache_stats()
+    assert s["lookups"] == B and s["builds"] == len({(sid, o.key_rem((sid, aux))) for sid, aux in distinct if sid != O.SID_ERROR})
+    # masked logits: the same 1,003 values in every row, so that the expectation stays small
+    x = ws.make_logits(5, 1, w.vocab.V, 1.0)
+    d_log = torch.from_numpy(np.repeat(x, B, axis=0)).cuda()
+    wg.apply_mask(d_log, d_mask)
+    want_rows = np.stack([O.apply_mask(x.copy(), rows[i:i + 1])[0] for i in range(len(distinct))]).view(np.uint32)
+    assert (H.host_logit_bits(d_log) == want_rows[pick]).all()
+    # next states: every request takes the first token its mask allows (or token 1 where none is)
+    tok_of = np.array([O.select_bit(r, 0) if r.any() else 1 for r in rows], dtype=np.int32)
+    toks = tok_of[pick]
+    h.advance(d_states, torch.from_numpy(toks).cuda())
+    nxt = o.advance(np.array(distinct, dtype=np.uint32), tok_of)
+    assert (H.host_states(d_states) == nxt[pick]).all()
+    # and the whole step in one call, with the cache cleared
+    d_states2 = H.dev_states(st)
+    h.cache_clear()
+    d_log2 = torch.from_numpy(np.repeat(x, B, axis=0)).cuda()
+    d_mask.fill_(0)
+    h.decode_step(d_states2, None, d_mask, d_log2)
+    assert (H.host_mask(d_mask) == rows[pick]).all()
+    assert (H.host_logit_bits(d_log2) == want_rows[pick]).all()
