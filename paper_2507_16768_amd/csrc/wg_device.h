@@ -8,8 +8,8 @@ namespace wg {
 
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;
 
-// The token ids are cut into kParts contiguous ranges (on 1024-token boundaries, so on 16-byte
-// boundaries of a mask row).  Every list of candidate tokens is kept per range, so that the
+// The token ids are cut into kParts contiguous ranges (on 2048-token boundaries, so on 256-byte
+// boundaries of a mask row; a class_scan workgroup takes kPartGroup tokens, all in one range).  Every list of candidate tokens is kept per range, so that the
 // row of a state key whose candidates all need a deep walk can be built by several workgroups,
 // each owning the words of its ranges, without any merging.
 constexpr uint32_t kParts = 8;
@@ -17,7 +17,7 @@ constexpr uint32_t kPartGroup = 2048;
 
 // What the kernels want to know about a class table without reading its 256 bytes: the bytes
 // that leave through exit A / exit B (as long as there are at most kMaxExitBytes of them on a
-// side), and whether most byte values are rejected.
+// side), which first look the class scan takes, and the folded set of byte values that do not stay.
 constexpr uint32_t kMaxExitBytes = 6;
 struct ClassInfo {
     uint8_t n_a, n_b;            // bytes of class EXIT_A / EXIT_B, or 0xFF: more than kMaxExitBytes

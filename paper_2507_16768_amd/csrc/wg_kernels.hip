@@ -2,14 +2,18 @@
 //
 //   lookup       : request state -> cache key, claims missing keys and class tables
 //                  (advance_lookup: after advancing the state by the sampled token)
-//   class_scan   : every vocabulary token against one checkpoint's byte-class table
-//                  (lane = token, table in LDS, 64-lane ballots pack the row words)
+//   class_scan   : every vocabulary token against one checkpoint's byte-class table: a first look
+//                  that settles most tokens with one instruction or table look-up each (64-lane
+//                  ballots pack the row words), the rest byte by byte through the table in LDS
 //   key_build    : a workgroup assembles the row of a missing key (or its words for one token
-//                  range) in LDS from the class index and the tokens that leave the state early
+//                  range) in LDS from the class index and the tokens that leave the state early,
+//                  which it finds in the vocabulary's indexes (byte order, byte pairs) or in the
+//                  class index's lists
 //   gather       : cached row -> bitmask[b]   (gather_apply: and -inf into the logits)
 //   apply        : logits <- -inf where the mask bit is 0
 //   masked_argmax: greedy choice under the mask, logits only read
 //   advance      : per-request walk of the sampled token
+//   forced_bytes : per request, the rest of the Write run its state lies in
 //   select       : harness sampler stand-in (k-th set bit of a row)
 //
 // No MFMA anywhere: the path is byte matching and memory traffic.
