@@ -93,8 +93,8 @@ typedef struct {
     uint64_t builds;        /* mask rows built (one per distinct missing key) */
     uint64_t uncached_builds;/* ... of which could not be kept because every cache row was taken */
     uint64_t class_scans;   /* vocabulary scans (one per distinct missing allow/wait class table) */
-    uint64_t entries_walked;/* early-exit tokens examined by the row builds */
-    uint64_t keys;          /* distinct masks the compiled instances can ask for */
+    uint64_t entries_walked;/* candidate tokens examined by the row builds (index ranges and class lists) */
+    uint64_t keys;          /* distinct masks the compiled instances can ask for (instances of one shape share theirs) */
     uint64_t cache_rows;    /* rows the cache can hold (wg_cache_resize) */
     uint64_t rows_in_use;   /* rows holding a mask since the last clear */
     uint64_t arena_bytes;   /* device bytes reserved for cached rows and class indexes */
@@ -137,7 +137,10 @@ void wg_vocab_destroy(wg_vocab_t v);
  * <eos>, $arg.  Identical template texts are parsed once and instantiated per args[i]
  * (args may be NULL when no template has holes).  start_states_out[i] (host, may be
  * NULL) receives the start state of instance i.  The resulting handle serves a
- * heterogeneous batch: state ids are global to the handle.
+ * heterogeneous batch: state ids are global to the handle.  Every instance has state ids of
+ * its own; instances whose states are equal one for one (the same structure instantiated with
+ * the same arguments) share their cache keys, so their masks are built and held once (the global
+ * cache of the section "Mask Generation and Global Caching").
  * wg_lower does the host part only (no GPU needed) and returns an inspectable table;
  * lmax is the longest token length the masks will be built for. */
 int wg_lower(const char *const *templates, const wg_args_t *args, uint32_t n_templates,
