@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwgrammar.so")
-SOURCES = ["wg_api.cpp", "wg_lower.cpp", "wg_regex.cpp", "wg_kernels.hip", "wg_topk.hip"]
+SOURCES = ["wg_api.cpp", "wg_lower.cpp", "wg_regex.cpp", "wg_vocab_index.cpp", "wg_kernels.hip", "wg_topk.hip"]
 HEADERS = ["wg_internal.h", "wg_device.h", "wg_order.h", os.path.join("..", "..", "include", "wg.h")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
          # packed-fp32 instruction selection is switched off for every kernel in this library

@@ -8,33 +8,6 @@ namespace wg {
 
 constexpr uint32_t kNoKey = 0xFFFFFFFFu;
 
-// The token ids are cut into kParts contiguous ranges (on 2048-token boundaries, so on 256-byte
-// boundaries of a mask row; a class_scan workgroup takes kPartGroup tokens, all in one range).  Every list of candidate tokens is kept per range, so that the
-// row of a state key whose candidates all need a deep walk can be built by several workgroups,
-// each owning the words of its ranges, without any merging.
-constexpr uint32_t kParts = 8;
-constexpr uint32_t kPartGroup = 2048;
-
-// What the kernels want to know about a class table without reading its 256 bytes: the bytes
-// that leave through exit A / exit B (as long as there are at most kMaxExitBytes of them on a
-// side), which first look the class scan takes, and the folded set of byte values that do not stay.
-constexpr uint32_t kMaxExitBytes = 6;
-struct ClassInfo {
-    uint8_t n_a, n_b;            // bytes of class EXIT_A / EXIT_B, or 0xFF: more than kMaxExitBytes
-    uint8_t scan, pad;           // SCAN_*: how class_scan takes its first look at a token
-    uint8_t a[kMaxExitBytes], b[kMaxExitBytes];
-    unsigned long long nonstay;  // SCAN_SIG: bit (x & 63) for every byte value x that does not stay (never 0)
-    unsigned long long pad2;
-};
-static_assert(sizeof(ClassInfo) == 32, "class info layout");
-// The first look class_scan takes at a token, chosen by what the table does with most bytes:
-//   SCAN_SIG   nearly every byte value stays (a free-text Wait): a token none of whose bytes folds
-//              onto a byte value that does not stay is all-stay, by one AND with its signature;
-//   SCAN_HEAD  most byte values are rejected (an allow list): the first byte decides most tokens;
-//   SCAN_CHUNK anything between: the first 8 bytes through the table.
-enum : uint8_t { SCAN_CHUNK = 0, SCAN_SIG = 1, SCAN_HEAD = 2 };
-constexpr uint8_t kManyExits = 0xFF;
-
 struct DeviceTable {
     const StateDesc *states;
     const uint8_t *classes;      // 256-byte class tables
@@ -44,15 +17,6 @@ struct DeviceTable {
     uint32_t lmax;
     uint32_t n_classes;
 };
-
-// A token that leaves a checkpoint state before its last byte: the part of a mask that
-// depends on what follows the state.  `off` bytes are consumed up to and including the
-// exit byte, `rem` bytes remain, the first of which is `first`.
-struct ExitEntry {
-    uint32_t tok;
-    uint8_t off, cls, first, rem;
-};
-static_assert(sizeof(ExitEntry) == 8, "entry layout");
 
 struct DeviceVocab {
     const uint8_t *bytes;        // CSR token bytes (padded by 8)

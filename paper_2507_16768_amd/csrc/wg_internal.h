@@ -40,6 +40,70 @@ struct Table {
     uint32_t flags = 0;
 };
 
+// The token ids are cut into kParts contiguous ranges (on 2048-token boundaries, so on 256-byte
+// boundaries of a mask row; a class_scan workgroup takes kPartGroup tokens, all in one range).  Every list of candidate tokens is kept per range, so that the
+// row of a state key whose candidates all need a deep walk can be built by several workgroups,
+// each owning the words of its ranges, without any merging.
+constexpr uint32_t kParts = 8;
+constexpr uint32_t kPartGroup = 2048;
+
+// What the kernels want to know about a class table without reading its 256 bytes: the bytes
+// that leave through exit A / exit B (as long as there are at most kMaxExitBytes of them on a
+// side), which first look the class scan takes, and the folded set of byte values that do not stay.
+constexpr uint32_t kMaxExitBytes = 6;
+struct ClassInfo {
+    uint8_t n_a, n_b;            // bytes of class EXIT_A / EXIT_B, or 0xFF: more than kMaxExitBytes
+    uint8_t scan, pad;           // SCAN_*: how class_scan takes its first look at a token
+    uint8_t a[kMaxExitBytes], b[kMaxExitBytes];
+    unsigned long long nonstay;  // SCAN_SIG: bit (x & 63) for every byte value x that does not stay (never 0)
+    unsigned long long pad2;
+};
+static_assert(sizeof(ClassInfo) == 32, "class info layout");
+// The first look class_scan takes at a token, chosen by what the table does with most bytes:
+//   SCAN_SIG   nearly every byte value stays (a free-text Wait): a token none of whose bytes folds
+//              onto a byte value that does not stay is all-stay, by one AND with its signature;
+//   SCAN_HEAD  most byte values are rejected (an allow list): the first byte decides most tokens;
+//   SCAN_CHUNK anything between: the first 8 bytes through the table.
+enum : uint8_t { SCAN_CHUNK = 0, SCAN_SIG = 1, SCAN_HEAD = 2 };
+constexpr uint8_t kManyExits = 0xFF;
+
+// A token that leaves a checkpoint state before its last byte: the part of a mask that
+// depends on what follows the state.  `off` bytes are consumed up to and including the
+// exit byte, `rem` bytes remain, the first of which is `first`.
+struct ExitEntry {
+    uint32_t tok;
+    uint8_t off, cls, first, rem;
+};
+static_assert(sizeof(ExitEntry) == 8, "entry layout");
+
+// The static indexes of a vocabulary (they depend on the token bytes only), as host arrays in
+// the layouts the kernels read.  Built once per vocabulary; wg_vocab_create copies them to the
+// device as they are.
+struct VocabIndex {
+    uint32_t V = 0, W = 0, row_stride = 0, lmax = 0, n_chunks = 0;
+    uint32_t part_tok[kParts + 1] = {};    // first token of each range; part_tok[kParts] == V
+    std::vector<uint8_t> bytes;            // the token bytes, 8 zero bytes behind them
+    std::vector<uint32_t> offsets;         // V + 1
+    std::vector<uint8_t> len8, first8;     // per token
+    std::vector<uint64_t> chunks;          // max(n_chunks, 1) * V
+    std::vector<uint64_t> sig;             // per token
+    std::vector<ExitEntry> lit_entries;    // never empty (one unused entry when no token has bytes)
+    std::vector<uint32_t> lit_start;       // 256 * kParts + 1
+    std::vector<uint32_t> len_rows;        // (lmax + 2) * row_stride
+    std::vector<ExitEntry> sorted;         // never empty
+    std::vector<uint32_t> dir0;            // 256 * 257 + 1
+    std::vector<ExitEntry> bigram;         // never empty
+    std::vector<uint32_t> dirN;            // 65536 + 1
+};
+
+// Checks the vocabulary arguments of wg_vocab_create and builds the indexes.  Returns WG_OK, or
+// an error code with the message in *err; `out` is then unspecified.
+int build_vocab_index(const uint8_t *host_bytes, const uint64_t *host_offsets, uint32_t V, int32_t eos_id,
+                      VocabIndex *out, std::string *err);
+
+// The summary of one 256-byte class table that the kernels read in its place.
+ClassInfo class_info_of(const uint8_t *table);
+
 // The host operator compiler with its memory: parsed template texts (the static structures)
 // and the class tables seen so far, so that instances can be added to a live table.
 struct LoweringState;

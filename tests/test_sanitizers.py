@@ -1,5 +1,5 @@
 """The host code under AddressSanitizer and UndefinedBehaviorSanitizer: the library's operator
-compiler and regular-expression translator and the C oracle are built with
+compiler, regular-expression translator and vocabulary index builder and the C oracle are built with
 -fsanitize=address,undefined into one driver (tests/sanitize/host_check.cpp) and run over
 workload templates with arguments, random operator trees, malformed templates, incremental
 adds with a failing add in between, and regular expressions.  Nothing here touches the GPU."""
@@ -12,7 +12,7 @@ import pytest
 import wg_synth as ws
 from wg_synth.configs import TreeGen
 from wg_synth.rng import Counter
-from wg_synth.vocab import tiny_vocab
+from wg_synth.vocab import from_tokens, make_vocab, tiny_vocab
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -25,7 +25,20 @@ def _hex(b):
 def _case_file(path):
     lines = []
     v = tiny_vocab(b"ab<.1,\"", 2)
-    lines.append("V %s %s %d" % (_hex(bytes(v.bytes)), ",".join(str(int(x)) for x in v.offsets), v.eos_id))
+
+    def vocab(v, eos_id=None):
+        lines.append("V %s %s %d" % (_hex(bytes(v.bytes)), ",".join(str(int(x)) for x in v.offsets),
+                                     v.eos_id if eos_id is None else eos_id))
+
+    # the static indexes of several vocabularies: token ranges that are empty, ragged or whole,
+    # multi-byte characters, duplicate and byte-less tokens, no end-of-sequence token
+    for big, eos in ((make_vocab(5000, ("geometric", 4, 16), seed=3, utf8_tenths=2), None), (make_vocab(2048, ("uniform", 1, 9), seed=4), None),
+                     (make_vocab(16385, ("geometric", 5, 24), seed=5), -1), (from_tokens([b"", b"a", b"a", b"ab", b"", b"\xff\xff\xff"], 0), None),
+                     (from_tokens([b"", b""], 1), None)):
+        vocab(big, eos)
+        lines.append("I")
+    vocab(v)
+    lines.append("I")
 
     def case(texts, args, flags, lmax, chunks=None):
         lines.append("C %d %d" % (flags, lmax))
@@ -73,6 +86,7 @@ def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
     for cc, std, src in (("gcc", "-std=c11", os.path.join(ROOT, "oracle", "wg_oracle.c")),
                          ("g++", "-std=c++17", os.path.join(csrc, "wg_lower.cpp")),
                          ("g++", "-std=c++17", os.path.join(csrc, "wg_regex.cpp")),
+                         ("g++", "-std=c++17", os.path.join(csrc, "wg_vocab_index.cpp")),
                          ("g++", "-std=c++17", os.path.join(ROOT, "tests", "sanitize", "host_check.cpp"))):
         obj = str(tmp_path / (os.path.basename(src) + ".o"))
         subprocess.run([cc, std, "-Wall"] + san + ["-c", src, "-o", obj], check=True, cwd=ROOT)
@@ -89,4 +103,5 @@ def test_host_code_is_clean_under_asan_and_ubsan(tmp_path):
     assert r.returncode == 0, tail
     assert "failures 0" in r.stdout and "MISMATCH" not in r.stdout, tail
     assert "ERROR: AddressSanitizer" not in r.stderr and "runtime error" not in r.stderr and "LeakSanitizer" not in r.stderr, tail
+    assert r.stdout.count("index ok ") == 6 and "INDEX" not in r.stdout, tail
     assert r.stdout.count("\nok ") > 100 and r.stdout.count("err") > 15, tail
