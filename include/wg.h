@@ -209,6 +209,14 @@ int wg_cache_resize(wg_handle_t h, uint32_t rows);
 int wg_reserve_batch(wg_handle_t h, uint32_t max_batch);
 uint32_t wg_max_batch(wg_handle_t h);       /* the current reservation */
 
+/* wg_set_scan_batch: how many of the class tables a call has to index (the context-free part of
+ * the masks, "Mask Generation and Global Caching": a mask depends on the allow / wait sets only)
+ * one workgroup takes through its share of the vocabulary together: 1 .. 8, or 0 (what wg_compile
+ * sets) to let each call choose -- one table while the call brings few, more as it brings many,
+ * and always one for a handle with few class tables.  A tuning knob: every setting gives the same
+ * masks.  Takes effect with the next call; a HIP graph recorded before keeps the old setting. */
+int wg_set_scan_batch(wg_handle_t h, uint32_t tables);
+
 uint32_t wg_num_states(wg_handle_t h);
 uint32_t wg_mask_words(wg_handle_t h);      /* W = ceil(V/32) */
 

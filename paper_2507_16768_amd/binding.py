@@ -57,7 +57,7 @@ EXPORTS = [
     "wg_last_error", "wg_select_tokens", "wg_profile_enable", "wg_profile_read", "wg_masked_argmax",
     "wg_add_instances", "wg_num_instances", "wg_cache_resize", "wg_table_add_instances",
     "wg_table_num_instances", "wg_advance_fill_masks", "wg_regex_to_template",
-    "wg_decode_step", "wg_masked_topk", "wg_masked_topk_workspace", "wg_reserve_batch", "wg_max_batch",
+    "wg_decode_step", "wg_masked_topk", "wg_masked_topk_workspace", "wg_reserve_batch", "wg_max_batch", "wg_set_scan_batch",
     "wg_masked_topk_static", "wg_masked_topk_static_capacity", "wg_profile_apply_mask", "wg_forced_bytes",
 ]
 
@@ -102,6 +102,7 @@ def load_library():
     L.wg_num_instances.restype = u32
     L.wg_cache_resize.argtypes = [vp, u32]
     L.wg_reserve_batch.argtypes = [vp, u32]
+    L.wg_set_scan_batch.argtypes = [vp, u32]
     L.wg_max_batch.argtypes = [vp]
     L.wg_max_batch.restype = u32
     L.wg_num_states.argtypes = [vp]
@@ -348,6 +349,9 @@ class Handle:
 
     def max_batch(self):
         return load_library().wg_max_batch(self._h)
+
+    def set_scan_batch(self, tables):
+        _check(load_library().wg_set_scan_batch(self._h, int(tables)))
 
     def cache_resize(self, rows):
         _check(load_library().wg_cache_resize(self._h, int(rows)))

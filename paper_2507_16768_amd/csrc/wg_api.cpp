@@ -30,13 +30,13 @@ struct wg_vocab_s {
     uint64_t *d_chunks = nullptr, *d_sig = nullptr;
     uint8_t *d_first8 = nullptr;
     ExitEntry *d_lit_entries = nullptr, *d_sorted = nullptr, *d_bigram = nullptr;
-    uint32_t *d_dir0 = nullptr, *d_dirN = nullptr;
+    uint32_t *d_dir0 = nullptr, *d_dirN = nullptr, *d_byte_rows = nullptr;
     int device = 0;
     void release() {
         (void)hipFree(d_bytes); (void)hipFree(d_len8); (void)hipFree(d_offsets);
         (void)hipFree(d_lit_start); (void)hipFree(d_len_rows); (void)hipFree(d_chunks);
         (void)hipFree(d_lit_entries); (void)hipFree(d_sorted); (void)hipFree(d_bigram);
-        (void)hipFree(d_dir0); (void)hipFree(d_dirN); (void)hipFree(d_sig); (void)hipFree(d_first8);
+        (void)hipFree(d_dir0); (void)hipFree(d_dirN); (void)hipFree(d_byte_rows); (void)hipFree(d_sig); (void)hipFree(d_first8);
     }
 };
 
@@ -285,13 +285,14 @@ int wg_vocab_create(const uint8_t *host_bytes, const uint64_t *host_offsets, uin
     if (e == hipSuccess) e = upload(&v->d_dir0, ix.dir0.data(), ix.dir0.size());
     if (e == hipSuccess) e = upload(&v->d_bigram, ix.bigram.data(), ix.bigram.size());
     if (e == hipSuccess) e = upload(&v->d_dirN, ix.dirN.data(), ix.dirN.size());
+    if (e == hipSuccess) e = upload(&v->d_byte_rows, ix.byte_rows.data(), ix.byte_rows.size());
     if (e != hipSuccess) {
         v->release();
         return fail(e == hipErrorOutOfMemory ? WG_ERR_NOMEM : WG_ERR_HIP,
                     std::string("wg_vocab_create: ") + hipGetErrorString(e));
     }
     v->dv = DeviceVocab{v->d_bytes, v->d_offsets, v->d_len8, v->d_chunks, v->d_sig, v->d_first8, v->d_lit_entries,
-                        v->d_lit_start, v->d_len_rows, v->d_sorted, v->d_dir0, v->d_bigram, v->d_dirN,
+                        v->d_lit_start, v->d_len_rows, v->d_sorted, v->d_dir0, v->d_bigram, v->d_dirN, v->d_byte_rows,
                         V, ix.W, eos_id, ix.lmax, ix.n_chunks, ix.row_stride, {}};
     for (uint32_t p = 0; p <= kParts; p++) v->dv.part_tok[p] = ix.part_tok[p];
     *out = v.release();
@@ -504,6 +505,13 @@ int wg_reserve_batch(wg_handle_t h, uint32_t max_batch) {
 }
 
 uint32_t wg_max_batch(wg_handle_t h) { return h ? h->max_batch : 0; }
+
+int wg_set_scan_batch(wg_handle_t h, uint32_t tables) {
+    if (!h) return fail(WG_ERR_INVALID, "wg_set_scan_batch: null handle");
+    if (tables > 8u) return fail(WG_ERR_INVALID, "wg_set_scan_batch: tables must be 0 .. 8");
+    h->dc.scan_batch = tables;
+    return WG_OK;
+}
 
 uint32_t wg_num_instances(wg_handle_t h) { return h ? (uint32_t)h->low.table.start.size() : 0; }
 uint32_t wg_num_states(wg_handle_t h) { return h ? h->dt.n_states : 0; }

@@ -39,6 +39,9 @@ struct DeviceVocab {
     // range e * 256 + y of dirN holds the places where y follows e.
     const ExitEntry *bigram;
     const uint32_t *dirN;        // 65536 + 1 boundaries into bigram
+    // The vocabulary by byte value, as token rows: row x (0 .. 255) holds the tokens that contain
+    // the byte x, row 256 + x the tokens whose first byte is x.
+    const uint32_t *byte_rows;   // 512 rows of row_stride words
     uint32_t V, W;
     int32_t eos_id;
     uint32_t lmax;
@@ -129,6 +132,7 @@ struct DeviceCache {
     uint32_t row_stride;         // words, multiple of 4
     uint32_t n_keys;
     uint32_t epoch;              // cache generation of this call
+    uint32_t scan_batch;         // class tables a class_scan work item takes together; 0: chosen per call
 };
 
 // ev, when not null, holds eight events: a begin / end pair for each of the four kernels of a fill.

@@ -94,6 +94,7 @@ struct VocabIndex {
     std::vector<uint32_t> dir0;            // 256 * 257 + 1
     std::vector<ExitEntry> bigram;         // never empty
     std::vector<uint32_t> dirN;            // 65536 + 1
+    std::vector<uint32_t> byte_rows;       // 512 rows of row_stride words: 256 by any byte, 256 by the first byte
 };
 
 // Checks the vocabulary arguments of wg_vocab_create and builds the indexes.  Returns WG_OK, or

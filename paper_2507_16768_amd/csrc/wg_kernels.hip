@@ -543,6 +543,363 @@ class_scan_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
 }
 
 // ---------------------------------------------------------------------------------------------
+// class_scan for a call that brings many class tables: a workgroup takes a 2048-token group
+// through up to kScanBatch tables together.  What a table-by-table pass pays once per table --
+// the chain first look -> queue -> byte-by-byte look -> list places -> stores, each link a trip
+// to memory -- is paid once per batch, and the byte-by-byte look runs on the queued tokens of
+// all the batch's tables, so on full wavefronts.
+//
+// The first look takes 32 tokens at a time, from the vocabulary's rows by byte value: the tokens
+// that contain a byte which does not stay are the OR of the rows of those bytes, and every other
+// token with bytes is all-stay; of the former, the tokens whose first byte is not rejected (an OR
+// of first-byte rows, of the rejected bytes and complemented when those are fewer) are queued,
+// the others are rejected by their first byte.  A side with more than kScanRowsMax rows lets
+// every token through instead, which costs work, not correctness: the queue may hold any token,
+// the byte-by-byte look decides.  That look has two stages: the first 8 bytes of every queued
+// token, then the longer tokens those 8 bytes did not decide, queued again so that they too fill
+// their wavefronts.
+// Results are the ones class_scan_kernel leaves (rows, lists, counters); the order of entries
+// inside a list differs, which no reader depends on.
+constexpr uint32_t kScanBatch = 8;        // class tables of one work item
+constexpr uint32_t kScanQueue = 4096;     // places of the queue for the byte-by-byte look
+constexpr uint32_t kScanLong = 1024;      // places of the queue for its second stage
+constexpr uint32_t kScanStage = 768;      // exit entries held in LDS before they leave
+constexpr uint32_t kScanRowsMax = 64;     // most rows ORed for one side of a table's first look
+constexpr uint32_t kScanRowsUnroll = 8;   // rows a wavefront requests together
+constexpr uint32_t kScanFixed = 3;        // what a work item costs before its first table, in tables
+constexpr uint32_t kScanBatchWgs = 5;     // workgroups of this kernel a compute unit holds (its LDS and registers)
+constexpr uint32_t kScanBatchFrom = 4096; // (class tables of a handle) x (token groups) above which it takes this kernel
+static_assert(kScanBatch <= 8u && kScanGroup <= 2048u, "a queue place holds table and token in 14 bits");
+static_assert(kScanStage <= 4096u && kScanThreads <= kScanStage, "the rank of a staged entry has 12 bits; a round's entries fit");
+static_assert(kScanThreads <= kScanLong && kScanGroup <= kScanQueue, "a round fits the second queue, a table's tokens the first");
+
+__global__ void __launch_bounds__(kScanThreads) __attribute__((amdgpu_waves_per_eu(5, 8)))
+class_scan_batch_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t lut[kScanBatch][256];
+    __shared__ uint32_t row_s[kScanBatch][kScanGroup / 32u], row_e[kScanBatch][kScanGroup / 32u];
+    __shared__ uint2 ent[kScanStage];                // early exits of the batch's tables, in the order found
+    __shared__ uint16_t meta[kScanStage];            // of a staged entry: table | long << 3 | rank in (table, side) << 4
+    __shared__ uint16_t que[kScanQueue];             // table << 11 | the token's place in the group
+    __shared__ uint16_t que_long[kScanLong];         // the same, tokens the first 8 bytes did not decide
+    __shared__ uint32_t acc[kScanBatch][2][kScanGroup / 32u];   // the ORs of the first look: [0] has a byte that does not stay, [1] by first byte
+    __shared__ uint16_t row_list[kScanBatch * 2u * kScanRowsMax];   // the rows to OR: table << 9 | row of byte_rows
+    __shared__ uint8_t first_inv[kScanBatch];        // the first-byte OR is of the rejected bytes
+    __shared__ uint32_t cls_s[kScanBatch];
+    __shared__ uint32_t n_ent[kScanBatch][2], list_base[kScanBatch][2][2];
+    __shared__ uint32_t n_rows, n_que, n_long, n_stage;
+    const uint32_t n = Cc.ctr->n_class_miss;
+    if (n == 0) return;
+    const uint32_t groups = (Vc.V + kScanGroup - 1u) / kScanGroup;
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6, tid = threadIdx.x;
+    const uint32_t V = Vc.V;
+    // how many of the lanes before this one are set in a ballot
+    auto before = [](unsigned long long bal) {
+        return (uint32_t)__builtin_amdgcn_mbcnt_hi((uint32_t)(bal >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)bal, 0u));
+    };
+    // (the same hand-out of token groups to XCDs as in class_scan_kernel)
+    const uint32_t nx = gridDim.x < kXcds ? gridDim.x : kXcds;
+    const uint32_t xcd = blockIdx.x % nx, local = blockIdx.x / nx;
+    const uint32_t local_wgs = (gridDim.x - xcd + nx - 1u) / nx;
+    const uint32_t my_groups = groups > xcd ? (groups - xcd + nx - 1u) / nx : 0u;
+    // Tables per work item.  The launch is one workgroup per place the chip has for this kernel,
+    // and a workgroup takes every local_wgs-th item of its XCD; an item costs a fixed part (the
+    // trips to memory of its chain) and a part per table.  The number of tables is the one under
+    // which the busiest XCD is done soonest by that count.
+    uint32_t per = Cc.scan_batch;
+    if (!per) {
+        const uint32_t most_groups = (groups + nx - 1u) / nx, fewest_wgs = gridDim.x / nx ? gridDim.x / nx : 1u;
+        uint32_t best = 0xFFFFFFFFu;
+        for (uint32_t p = 1; p <= kScanBatch; p++) {
+            const uint64_t wide = (uint64_t)((n + p - 1u) / p) * most_groups;
+            const uint32_t items = wide > 0x7FFFFFFFull ? 0x7FFFFFFFu : (uint32_t)wide;
+            const uint32_t cost = ((items + fewest_wgs - 1u) / fewest_wgs) * (kScanFixed + p);
+            if (cost < best) { best = cost; per = p; }
+        }
+    }
+    per = per < 1u ? 1u : per > kScanBatch ? kScanBatch : per;
+    const uint32_t batches = (n + per - 1u) / per;
+    const uint64_t total = (uint64_t)batches * my_groups;
+    for (uint64_t item = local; item < total; item += local_wgs) {
+        const uint32_t t0 = (uint32_t)(item / my_groups) * per;
+        const uint32_t nt = n - t0 < per ? n - t0 : per;
+        const uint32_t g = (uint32_t)(item % my_groups) * nx + xcd;
+        // the tokens of this thread's word of the group that have bytes (none beyond V)
+        const uint32_t word_hb = g * (kScanGroup / 32u) + (tid >> 2);
+        const uint32_t has_bytes = word_hb < Vc.row_stride ? Vc.len_rows[(size_t)(Vc.lmax + 1u) * Vc.row_stride + word_hb] : 0u;
+        uint32_t part = 0;
+#pragma unroll
+        for (uint32_t q = 1; q < kParts; q++) part += g * kScanGroup >= Vc.part_tok[q];
+        const uint32_t out_lo = V + Vc.part_tok[part], out_hi = V + Vc.part_tok[part + 1u];
+        if (tid == 0) { n_rows = 0; n_que = 0; n_long = 0; n_stage = 0; }   // (the item before is past their last use)
+        __syncthreads();                             // the item before is done with the LDS
+        // The tables come in, a wavefront one table at a time, a lane 4 of its byte values; what
+        // the lanes see of the table says which rows its first look ORs.
+        for (uint32_t i = tid; i < nt * 64u; i += kScanThreads) {
+            const uint32_t t = i >> 6;               // (the same for the whole wavefront)
+            const uint32_t c = Cc.class_miss[t0 + t];
+            const uint32_t cw = reinterpret_cast<const uint32_t *>(T.classes + (size_t)c * 256u)[lane];
+            reinterpret_cast<uint32_t *>(lut[t])[lane] = cw;
+            unsigned long long moves[4], lives[4];   // per byte value 4 * lane + k: does not stay / is not rejected
+            uint32_t n_moves = 0, n_lives = 0;
+#pragma unroll
+            for (uint32_t k = 0; k < 4u; k++) {
+                const uint32_t cl = (cw >> (8u * k)) & 0xFFu;
+                moves[k] = __ballot(cl != CLS_STAY);
+                lives[k] = __ballot(cl != CLS_REJECT);
+                n_moves += (uint32_t)__popcll(moves[k]);
+                n_lives += (uint32_t)__popcll(lives[k]);
+            }
+            const bool all_a = n_moves > kScanRowsMax;
+            const bool inv = n_lives > kScanRowsMax, all_b = inv && 256u - n_lives > kScanRowsMax;
+            const uint32_t cnt_a = all_a ? 0u : n_moves, cnt_b = all_b ? 0u : inv ? 256u - n_lives : n_lives;
+            row_e[t][lane] = 0;
+            acc[t][0][lane] = all_a ? 0xFFFFFFFFu : 0u;
+            acc[t][1][lane] = all_b ? 0xFFFFFFFFu : 0u;
+            uint32_t at = 0;
+            if (lane == 0) {
+                cls_s[t] = c; n_ent[t][0] = 0; n_ent[t][1] = 0; first_inv[t] = inv && !all_b;
+                if (cnt_a + cnt_b) at = atomicAdd(&n_rows, cnt_a + cnt_b);
+            }
+            at = __shfl(at, 0);
+#pragma unroll
+            for (uint32_t k = 0; k < 4u; k++) {
+                if (!all_a) {
+                    if ((moves[k] >> lane) & 1ull)
+                        row_list[at + before(moves[k])] = (uint16_t)(t << 9 | (4u * lane + k));
+                    at += (uint32_t)__popcll(moves[k]);
+                }
+            }
+#pragma unroll
+            for (uint32_t k = 0; k < 4u; k++) {
+                if (!all_b) {
+                    const unsigned long long pick = inv ? ~lives[k] : lives[k];
+                    if ((pick >> lane) & 1ull)
+                        row_list[at + before(pick)] = (uint16_t)(t << 9 | 256u | (4u * lane + k));
+                    at += (uint32_t)__popcll(pick);
+                }
+            }
+        }
+        __syncthreads();
+
+        uint32_t stage_bound = 0, que_bound = 0, long_bound = 0;   // no fewer than n_stage / n_que / n_long, known without a look
+        // The staged entries leave: per table and side, a run in the list of the whole table and a
+        // run in the list of the token range, their places taken with one atomic each.
+        // (Called by the whole workgroup, after a barrier that follows the last staged entry.)
+        auto flush = [&]() {
+            const uint32_t ns = n_stage;
+            if (tid < nt * 4u) {
+                const uint32_t t = tid >> 2, side = tid & 1u, which = (tid >> 1) & 1u;
+                const uint32_t cnt = n_ent[t][side];
+                const uint32_t ctr = which ? 2u + 2u * part + side : side;
+                list_base[t][which][side] = cnt ? atomicAdd(&Cc.class_count[cls_s[t] * kCountStride + ctr], cnt) : 0u;
+            }
+            __syncthreads();
+            for (uint32_t i = tid; i < ns; i += kScanThreads) {
+                const uint2 e = ent[i];
+                const uint32_t m = meta[i], t = m & 7u, r = m >> 4;
+                uint2 *out = reinterpret_cast<uint2 *>(Cc.class_entries[cls_s[t]]);
+                if (!(m & 8u)) {
+                    out[list_base[t][0][0] + r] = e;
+                    out[out_lo + list_base[t][1][0] + r] = e;
+                } else {
+                    out[V - 1u - (list_base[t][0][1] + r)] = e;
+                    out[out_hi - 1u - (list_base[t][1][1] + r)] = e;
+                }
+            }
+            __syncthreads();
+            if (tid < nt * 2u) n_ent[tid >> 1][tid & 1u] = 0;
+            if (tid == 0) n_stage = 0;
+            stage_bound = 0;
+            __syncthreads();
+        };
+        // Room in the staging list for the entries of one more round (every thread takes the same way).
+        auto stage_room = [&]() {
+            if (stage_bound + kScanThreads > kScanStage) {
+                // count exactly, between two barriers so that every thread reads the same number
+                __syncthreads();
+                const uint32_t staged = n_stage;
+                __syncthreads();
+                if (staged + kScanThreads > kScanStage) flush();
+                else stage_bound = staged;
+            }
+            stage_bound += kScanThreads;
+        };
+        // What the byte-by-byte look found for a token goes to the rows and the staging list: the
+        // first byte that does not stay is byte j with class res (1: none, all bytes stay).
+        auto settle = [&](uint32_t t, uint32_t idx, uint32_t tok, uint32_t Lq, uint32_t res, uint32_t j, uint32_t first) {
+            const bool exits = res >= 2u;
+            if (res == 1u) atomicOr(&row_s[t][idx >> 5], 1u << (idx & 31u));
+            if (exits && j + 1u == Lq) atomicOr(&row_e[t][idx >> 5], 1u << (idx & 31u));
+            const uint32_t nxt = j + 1u;
+            const bool early = exits && nxt < Lq;
+            const unsigned long long be = __ballot(early);
+            if (!be) return;
+            uint32_t base = 0;
+            if (lane == 0) base = atomicAdd(&n_stage, (uint32_t)__popcll(be));
+            base = __shfl(base, 0);
+            if (early) {
+                const uint32_t rem = Lq - nxt, side = rem > kShortRem;
+                const uint32_t r = atomicAdd(&n_ent[t][side], 1u);
+                const uint32_t at = base + before(be);
+                ent[at] = uint2{tok, nxt | res << 8 | first << 16 | rem << 24};
+                meta[at] = (uint16_t)(t | side << 3 | r << 4);
+            }
+        };
+        // Second stage: the tokens longer than 8 bytes whose first 8 all stay, from byte 8 on.
+        // (Called by the whole workgroup, after a barrier that follows the last write to its queue.)
+        auto drain_long = [&]() {
+            const uint32_t nl = n_long;
+            __syncthreads();                         // every thread has read the length
+            for (uint32_t i0 = 0; i0 < nl; i0 += kScanThreads) {
+                stage_room();
+                if (i0 + wave * 64u >= nl) continue;                    // nothing for this wavefront in the last round
+                const bool act = i0 + tid < nl;
+                const uint32_t q = que_long[act ? i0 + tid : 0u];
+                const uint32_t t = q >> 11, idx = q & (kScanGroup - 1u);
+                const uint32_t tok = g * kScanGroup + idx;               // below V
+                const uint32_t Lq = act ? Vc.len8[tok] : 0u;             // above 8
+                const uint64_t d1 = Vc.chunks[(Vc.n_chunks > 1u ? (size_t)V : 0u) + tok];
+                const uint64_t d2 = Vc.chunks[(Vc.n_chunks > 2u ? 2ull * V : 0ull) + tok];
+                uint32_t res = 0, j = 0;
+                if (Lq) {
+                    bool decided = scan_chunk(lut[t], d1, Lq, 1, res, j);
+                    if (!decided) decided = scan_chunk(lut[t], d2, Lq, 2, res, j);
+                    for (uint32_t k = 3; k < Vc.n_chunks && !decided; k++)
+                        decided = scan_chunk(lut[t], Vc.chunks[(size_t)k * V + tok], Lq, k, res, j);
+                }
+                uint32_t first = 0;
+                if (res >= 2u && j + 1u < Lq) {
+                    const uint32_t nxt = j + 1u;
+                    if (nxt < 24u) first = (uint32_t)((nxt < 16u ? d1 : d2) >> (8u * (nxt & 7u))) & 0xFFu;
+                    else first = Vc.bytes[Vc.offsets[tok] + nxt];
+                }
+                settle(t, idx, tok, Lq, res, j, first);
+            }
+            __syncthreads();                         // the rounds are over
+            if (tid == 0) n_long = 0;
+            long_bound = 0;
+            __syncthreads();
+        };
+        // First stage: the first 8 bytes of every queued token, one token per thread and round.
+        // (Called by the whole workgroup, after a barrier that follows the last write to the queue.)
+        auto drain = [&]() {
+            const uint32_t nq = n_que;
+            __syncthreads();                         // every thread has read the length
+            for (uint32_t i0 = 0; i0 < nq; i0 += kScanThreads) {
+                stage_room();
+                if (long_bound + kScanThreads > kScanLong) {
+                    // the second queue may be short of room for a round: count exactly, empty it if need be
+                    __syncthreads();
+                    const uint32_t waiting = n_long;
+                    __syncthreads();
+                    if (waiting + kScanThreads > kScanLong) drain_long();
+                    else long_bound = waiting;
+                }
+                long_bound += kScanThreads;
+                if (i0 + wave * 64u >= nq) continue;                    // nothing for this wavefront in the last round
+                const bool act = i0 + tid < nq;
+                const uint32_t q = que[act ? i0 + tid : 0u];
+                const uint32_t t = q >> 11, idx = q & (kScanGroup - 1u);
+                const uint32_t tok = g * kScanGroup + idx;               // below V
+                const uint32_t Lq = act ? Vc.len8[tok] : 0u;
+                const uint64_t d0 = Vc.chunks[tok];
+                uint32_t res = 0, j = 0;
+                const bool decided = Lq == 0u || scan_chunk(lut[t], d0, Lq, 0, res, j);
+                // undecided: to the second queue
+                const unsigned long long bu = __ballot(!decided);
+                if (bu) {
+                    uint32_t base = 0;
+                    if (lane == 0) base = atomicAdd(&n_long, (uint32_t)__popcll(bu));
+                    base = __shfl(base, 0);
+                    if (!decided) que_long[base + before(bu)] = (uint16_t)q;
+                }
+                uint32_t first = 0;
+                if (decided && res >= 2u && j + 1u < Lq) {
+                    const uint32_t nxt = j + 1u;     // at most 8
+                    first = nxt < 8u ? (uint32_t)(d0 >> (8u * nxt)) & 0xFFu : (uint32_t)Vc.chunks[(size_t)V + tok] & 0xFFu;
+                }
+                settle(t, idx, tok, decided ? Lq : 0u, decided ? res : 0u, j, first);
+            }
+            __syncthreads();                         // the rounds are over: the second queue is written
+            if (tid == 0) n_que = 0;
+            que_bound = 0;
+            __syncthreads();
+        };
+
+        // First look, the ORs: a lane takes one word (32 tokens) of the group, a wavefront every
+        // fourth stretch of kScanRowsUnroll rows of the list, requested together; the ORs meet in LDS.
+        {
+            const uint32_t gw = g * (kScanGroup / 32u) + lane;
+            const bool in_row = gw < Vc.row_stride;
+            const uint32_t nr = n_rows;
+            for (uint32_t base = wave * kScanRowsUnroll; base < nr; base += 4u * kScanRowsUnroll) {
+                uint32_t code[kScanRowsUnroll], x[kScanRowsUnroll];
+#pragma unroll
+                for (uint32_t u = 0; u < kScanRowsUnroll; u++) {
+                    code[u] = row_list[base + u < nr ? base + u : base];
+                    x[u] = in_row ? Vc.byte_rows[(size_t)(code[u] & 511u) * Vc.row_stride + gw] : 0u;
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < kScanRowsUnroll; u++)
+                    if (base + u < nr && x[u]) atomicOr(&acc[code[u] >> 9][(code[u] >> 8) & 1u][lane], x[u]);
+            }
+        }
+        __syncthreads();
+        // First look, the tokens: a thread takes a byte of a word (8 tokens): all-stay tokens go to
+        // the row, queued ones take their places in the queue.
+        for (uint32_t t = 0; t < nt; t++) {
+            if (que_bound + kScanGroup > kScanQueue) {
+                // the queue may be short of room for a whole group: count exactly, empty it if need be
+                __syncthreads();
+                const uint32_t waiting = n_que;
+                __syncthreads();
+                if (waiting + kScanGroup > kScanQueue) drain();
+                else que_bound = waiting;
+            }
+            que_bound += kScanGroup;
+            const uint32_t wd = tid >> 2, bi = tid & 3u;
+            const uint32_t a = acc[t][0][wd];
+            const uint32_t b = first_inv[t] ? ~acc[t][1][wd] : acc[t][1][wd];
+            if (bi == 0) row_s[t][wd] = ~a & has_bytes;
+            const uint32_t mine = ((a & b & has_bytes) >> (8u * bi)) & 0xFFu;
+            // places in the queue: one LDS atomic per wavefront; a token's place follows from the
+            // ballots of the 8 token positions of a thread
+            unsigned long long bal[8];
+            uint32_t n_mine = 0;
+#pragma unroll
+            for (uint32_t j = 0; j < 8u; j++) {
+                bal[j] = __ballot((mine >> j) & 1u);
+                n_mine += (uint32_t)__popcll(bal[j]);
+            }
+            uint32_t at = 0;
+            if (lane == 0 && n_mine) at = atomicAdd(&n_que, n_mine);
+            at = __shfl(at, 0);
+#pragma unroll
+            for (uint32_t j = 0; j < 8u; j++) {
+                if ((mine >> j) & 1u)
+                    que[at + before(bal[j])] = (uint16_t)(t << 11 | (wd * 32u + bi * 8u + j));
+                at += (uint32_t)__popcll(bal[j]);
+            }
+        }
+        __syncthreads();
+        drain();
+        drain_long();
+        if (n_stage) flush();                        // (read behind the barrier that ends drain_long, the same for every thread)
+        for (uint32_t i = tid; i < nt * (kScanGroup / 32u); i += kScanThreads) {
+            const uint32_t t = i / (kScanGroup / 32u), wd = i % (kScanGroup / 32u);
+            const uint32_t w = g * (kScanGroup / 32u) + wd;
+            if (w < Vc.W) {
+                uint32_t *rows = Cc.class_rows + (size_t)(3u * cls_s[t]) * Cc.row_stride;
+                const uint32_t a = row_s[t][wd], b = row_e[t][wd];
+                rows[w] = a; rows[Cc.row_stride + w] = b; rows[2u * Cc.row_stride + w] = a | b;
+            }
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) atomicAdd(&Cc.ctr->class_scans, (unsigned long long)n);
+}
+
+// ---------------------------------------------------------------------------------------------
 // key_build: a workgroup assembles the mask row of a missing state key in LDS -- or, for a key
 // whose candidates all need a deep walk, its words for one of the kParts token ranges, so that
 // such a key is shared among kParts workgroups instead of holding up the whole launch:
@@ -1336,8 +1693,14 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
     uint32_t groups = cdiv(Vc.V, kScanGroup);
     uint64_t scan_items = (uint64_t)B * groups;
     uint32_t cap = n_cu * 8u;
-    launch(class_scan_kernel, dim3(scan_items < cap ? (uint32_t)scan_items : cap), dim3(kScanThreads), 0, s,
-           ev ? ev + 2 : nullptr, T, Vc, Cc);
+    // a handle with few class tables scans them one per work item; with many, a call may bring so
+    // many that they are taken several at a time
+    if (Cc.scan_batch ? Cc.scan_batch > 1u : (uint64_t)T.n_classes * groups > kScanBatchFrom)
+        launch(class_scan_batch_kernel, dim3(scan_items < n_cu * kScanBatchWgs ? (uint32_t)scan_items : n_cu * kScanBatchWgs),
+               dim3(kScanThreads), 0, s, ev ? ev + 2 : nullptr, T, Vc, Cc);
+    else
+        launch(class_scan_kernel, dim3(scan_items < cap ? (uint32_t)scan_items : cap), dim3(kScanThreads), 0, s,
+               ev ? ev + 2 : nullptr, T, Vc, Cc);
     // up to kParts work items per key; two 512-thread workgroups fit a compute unit
     const uint32_t kb = n_cu * 2u;
     const uint64_t kb_items = (uint64_t)B * kParts;

@@ -151,13 +151,20 @@ int build(const uint8_t *host_bytes, const uint64_t *host_offsets, uint32_t V, i
                 bigram[at[(uint32_t)bytes[off[t] + i - 1] << 8 | bytes[off[t] + i]]++] = e;
             }
     }
+    // The vocabulary by byte value, as rows of tokens (which tokens contain the byte x, which start
+    // with it): a class table's first look at 32 tokens is then the OR of a few words.
+    std::vector<uint32_t> byte_rows((size_t)512 * rs, 0);
+    for (uint32_t t = 0; t < V; t++) {
+        for (uint32_t i = 0; i < len8[t]; i++) byte_rows[(size_t)bytes[off[t] + i] * rs + (t >> 5)] |= 1u << (t & 31u);
+        if (len8[t]) byte_rows[(size_t)(256u + first8[t]) * rs + (t >> 5)] |= 1u << (t & 31u);
+    }
     VocabIndex &ix = *out;
     ix.V = V; ix.W = W; ix.row_stride = rs; ix.lmax = lmax; ix.n_chunks = n_chunks;
     for (uint32_t p = 0; p <= kParts; p++) ix.part_tok[p] = part_tok[p];
     ix.bytes.swap(bytes); ix.offsets.swap(off); ix.len8.swap(len8); ix.first8.swap(first8);
     ix.chunks.swap(chunks); ix.sig.swap(sig); ix.lit_entries.swap(lit_entries); ix.lit_start.swap(lit_start);
     ix.len_rows.swap(len_rows); ix.sorted.swap(sorted); ix.dir0.swap(dir0); ix.bigram.swap(bigram);
-    ix.dirN.swap(dirN);
+    ix.dirN.swap(dirN); ix.byte_rows.swap(byte_rows);
     return WG_OK;
 }
 

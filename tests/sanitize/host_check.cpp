@@ -164,6 +164,17 @@ static void check_index(const uint8_t *vb, const uint64_t *off, uint32_t V, int3
             }
         }
     }
+    // the vocabulary by byte value as token rows: tokens that contain the byte, tokens that start with it
+    EXPECT(ix.byte_rows.size() == (size_t)512 * ix.row_stride, "byte rows size");
+    {
+        std::vector<uint32_t> want((size_t)512 * ix.row_stride, 0);
+        for (uint32_t t = 0; t < V; t++)
+            for (uint32_t i = 0; i < len(t); i++) {
+                want[(size_t)byte_at(t, i) * ix.row_stride + t / 32] |= 1u << (t % 32);
+                if (i == 0) want[(size_t)(256 + byte_at(t, 0)) * ix.row_stride + t / 32] |= 1u << (t % 32);
+            }
+        for (size_t i = 0; i < want.size(); i++) EXPECT(ix.byte_rows[i] == want[i], "byte row %zu word %zu", i / ix.row_stride, i % ix.row_stride);
+    }
     std::printf("index ok %u %u %llu\n", V, with_bytes, (unsigned long long)pairs);
 }
 

@@ -329,6 +329,70 @@ def test_every_kind_of_class_table_and_candidate_source(torch_cuda):
         assert (H.host_states(d_st) == o.advance(rep_states, tk)).all(), t
 
 
+@pytest.mark.parametrize("tables", [0, 1, 2, 3, 8])
+def test_class_tables_scanned_several_at_a_time(torch_cuda, tables):
+    """wg_set_scan_batch: a workgroup of the class scan takes 1, 2, 3 or 8 class tables through its
+    tokens together (0: the call chooses).  Checkpoints chosen so that every path of the batched
+    scan is taken on a 20,011-token vocabulary (10 token groups, the last ragged): tables that
+    queue nearly every token for the byte-by-byte look (the queue is emptied between tables), tables
+    under which nearly every token leaves an exit entry (the staged entries leave more than once per
+    work item), free text, allow lists, a table no byte leaves; 19 templates bring more tables
+    than a batch holds, with a last batch that is not full.  Every state and budget against the
+    oracle, cold, then cold again after a clear, then warm; then every state of a reduced config 5."""
+    torch = torch_cuda
+    base = ws.make_workload(2, V=20011, B=1, steps=1)
+    texts = []
+    for i in range(8):        # one allowed letter, every other printable byte leaves: an exit entry per token
+        a = chr(ord("a") + i)
+        texts.append(r'Sequence(Wait(allow={%s}, wait={[\x20-\x60], [\x7b-\x7e], %s}), Write("%s."))'
+                     % (a, ", ".join(chr(c) for c in range(ord("a"), ord("z") + 1) if chr(c) != a), a))
+    for i in range(6):        # printable text up to one byte: most tokens need the byte-by-byte look
+        texts.append(r'Sequence(Wait(allow={[\x20-\x7e]}, wait={%s}, max=%d), Write("ok"))'
+                     % (("<", ">", r"\x7b", r"\x7d", r"\x5b", r"\x5d")[i], 3 + i))
+    texts += [
+        r'Sequence(Wait(denies={}, wait={\n}), Write("x"))',
+        r'Sequence(Wait(allow={\d}, wait={;}), Wait(allow={[a-f]}, wait={\,}, max=4))',
+        r'Sequence(Write("q"), Wait(allow={[\x00-\xff]}, wait={<eos>}))',
+        r'IfElse(condition=Wait(allow={\s}, true_waits={[0-6]}, false_waits={[a-f]}), if_body=Write("x1"), else_body=None)',
+        r'DoWhile(body=Write("k"), condition=Wait(allow={\ }, true_waits={\,}, false_waits={\.}))',
+    ]
+    import dataclasses
+    w = dataclasses.replace(base, texts=texts, args=[{}] * len(texts), B=len(texts),
+                            request_template=np.arange(len(texts), dtype=np.int64))
+
+    def every_state(o):
+        st = []
+        for sid in range(1, o.num_states):
+            d = o.describe(sid)
+            st.append([sid, 0])
+            if d["kind"] == "WAIT" and d["max"] >= 0:
+                st += [[sid, a] for a in range(1, d["max"] + 2)]
+        return np.array(st, dtype=np.uint32)
+
+    for label, wl in (("chosen", w), ("config 5", ws.make_workload(5, V=7013, B=16, steps=1))):
+        print(label, tables, flush=True)
+        o = H.make_oracle(wl)
+        v, h = H.make_gpu(wl)
+        h.set_scan_batch(tables)
+        st = every_state(o)
+        h.reserve_batch(len(st))
+        want = o.fill_masks(st)
+        d_mask = torch.empty((len(st), h.W), dtype=torch.int32, device="cuda")
+        for rep in ("cold", "cleared", "warm"):
+            if rep == "cleared":
+                h.cache_clear()
+            d_mask.fill_(0x66666666)
+            h.fill_masks(H.dev_states(st), d_mask)
+            got = H.host_mask(d_mask)
+            bad = np.nonzero((got != want).any(axis=1))[0]
+            assert len(bad) == 0, (label, rep, st[bad[0]], o.describe(int(st[bad[0], 0])))
+        s = h.cache_stats()
+        assert s["class_scans"] >= (38 if label == "chosen" else 20) and s["hits"] == len(st), s
+        assert h.error_count() == 0
+    with pytest.raises(Exception):
+        h.set_scan_batch(9)
+
+
 @pytest.mark.timeout(600)
 def test_the_largest_batch_one_call_takes(torch_cuda):
     """B = 65,535 requests in one call (the most a call takes; one more is refused): masks, masked
