@@ -787,7 +787,6 @@ class_scan_batch_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
             const uint32_t nq = n_que;
             __syncthreads();                         // every thread has read the length
             for (uint32_t i0 = 0; i0 < nq; i0 += kScanThreads) {
-                stage_room();
                 if (long_bound + kScanThreads > kScanLong) {
                     // the second queue may be short of room for a round: count exactly, empty it if need be
                     __syncthreads();
@@ -797,6 +796,7 @@ class_scan_batch_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
                     else long_bound = waiting;
                 }
                 long_bound += kScanThreads;
+                stage_room();                        // (after the second stage may have run: it stages entries too)
                 if (i0 + wave * 64u >= nq) continue;                    // nothing for this wavefront in the last round
                 const bool act = i0 + tid < nq;
                 const uint32_t q = que[act ? i0 + tid : 0u];

@@ -338,7 +338,9 @@ def test_class_tables_scanned_several_at_a_time(torch_cuda, tables):
     under which nearly every token leaves an exit entry (the staged entries leave more than once per
     work item), free text, allow lists, a table no byte leaves; 19 templates bring more tables
     than a batch holds, with a last batch that is not full.  Every state and budget against the
-    oracle, cold, then cold again after a clear, then warm; then every state of a reduced config 5."""
+    oracle, cold, then cold again after a clear, then warm; then the same on a vocabulary of 5,000
+    tokens longer than 8 bytes that all leave their checkpoint after the eighth byte, and on every
+    state of a reduced config 5."""
     torch = torch_cuda
     base = ws.make_workload(2, V=20011, B=1, steps=1)
     texts = []
@@ -369,7 +371,24 @@ def test_class_tables_scanned_several_at_a_time(torch_cuda, tables):
                 st += [[sid, a] for a in range(1, d["max"] + 2)]
         return np.array(st, dtype=np.uint32)
 
-    for label, wl in (("chosen", w), ("config 5", ws.make_workload(5, V=7013, B=16, steps=1))):
+    # long tokens: 8 to 15 letters a, then b, then a tail; under a table that lets a stay and leaves
+    # at b, the first 8 bytes decide none of them, so all go through the second stage of the
+    # byte-by-byte look and leave their exit entries from there (its queue fills and is emptied
+    # between rounds of the first stage, the staged entries leave between rounds of the second)
+    from wg_synth.vocab import from_tokens
+    long_tokens = [b""] + [bytes([x]) for x in b"abcdefgh<."]
+    for i in range(5000):
+        tail = bytes(ord("c") + (i // 24 ** k) % 24 for k in range(3))      # i in base 24: no two alike
+        long_tokens.append(b"a" * (8 + i % 8) + b"b" + tail)
+        if i % 5 == 0:
+            long_tokens.append(b"a" * (1 + i % 4) + b"b" + tail)            # short ones between them
+    long_texts = [r'Sequence(Wait(allow={a, %s}, wait={b}), Wait(allow={[c-z]}, wait={.}))' % chr(ord("c") + i)
+                  for i in range(9)]                 # every tail is allowed behind the b: a lost exit entry is a lost token
+    long_w = dataclasses.replace(base, vocab=from_tokens(long_tokens, eos_id=0), texts=long_texts, args=[{}] * len(long_texts),
+                                 B=len(long_texts), request_template=np.arange(len(long_texts), dtype=np.int64))
+    assert len(set(long_tokens)) == len(long_tokens) and long_w.vocab.lmax <= 24
+
+    for label, wl in (("chosen", w), ("long tokens", long_w), ("config 5", ws.make_workload(5, V=7013, B=16, steps=1))):
         print(label, tables, flush=True)
         o = H.make_oracle(wl)
         v, h = H.make_gpu(wl)
@@ -387,7 +406,7 @@ def test_class_tables_scanned_several_at_a_time(torch_cuda, tables):
             bad = np.nonzero((got != want).any(axis=1))[0]
             assert len(bad) == 0, (label, rep, st[bad[0]], o.describe(int(st[bad[0], 0])))
         s = h.cache_stats()
-        assert s["class_scans"] >= (38 if label == "chosen" else 20) and s["hits"] == len(st), s
+        assert s["class_scans"] >= {"chosen": 38, "long tokens": 18, "config 5": 20}[label] and s["hits"] == len(st), s
         assert h.error_count() == 0
     with pytest.raises(Exception):
         h.set_scan_batch(9)
