@@ -648,6 +648,11 @@ def main():
         "cold": {"ms_per_step_passes": [s * 1e3 for s in cold_passes],
                  "keys_built_per_step": builds_per_step, "class_scans_per_step": scans_per_step,
                  "exit_entries_per_step": entries_per_step,
+                 # token bytes taken through a checkpoint's byte table per second: by the class scan
+                 # (every token once per scanned table, over the scan's own time), and what a walk of
+                 # the whole vocabulary per built key would have to sustain at this step time
+                 "byte_steps_per_s": {"class_scan": scans_per_step * sum_len / (kt_cold["scan_us"] * 1e-6) if kt_cold["scan_us"] > 0 else None,
+                                      "scan_per_key_dense_equivalent": builds_per_step * sum_len / sec_cold},
                  "method_bytes_per_step": method_bytes_cold,
                  "step_frac_method_bytes": method_bytes_cold / sec_cold / 1e9 / HBM_PEAK_GBS,
                  "dense_equivalent_GBs": dense_cold / sec_cold / 1e9,
