@@ -570,10 +570,13 @@ def main():
                        "cold_ms_per_step": sec_greedy_cold * 1e3, "warm_ms_per_step": sec_greedy_warm * 1e3,
                        "cold_request_steps_per_s": B / sec_greedy_cold, "warm_request_steps_per_s": B / sec_greedy_warm,
                        "masked_argmax_us": argmax_us,
-                       "masked_argmax_dense_read_GBs": B * (row_b + esz * V) / (argmax_us * 1e-6) / 1e9},
+                       "masked_argmax_dense_read_GBs": B * (row_b + esz * V) / (argmax_us * 1e-6) / 1e9,
+                       # the logits and the mask read once are this call's algorithmic bytes
+                       "masked_argmax_frac_of_hbm_peak": B * (row_b + esz * V) / (argmax_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
             "topk": {"note": "wg_masked_topk on the masks of the timed steps, k = %d; logits are read, never written" % topk_k,
                      "k": topk_k, "masked_topk_us": topk_us,
-                     "masked_topk_dense_read_GBs": B * (row_b + esz * V) / (topk_us * 1e-6) / 1e9},
+                     "masked_topk_dense_read_GBs": B * (row_b + esz * V) / (topk_us * 1e-6) / 1e9,
+                     "masked_topk_frac_of_hbm_peak": B * (row_b + esz * V) / (topk_us * 1e-6) / 1e9 / HBM_PEAK_GBS},
             "host_setup": {"vocabulary_indexes_ms": vocab_ms, "compile_all_instances_ms": compile_ms,
                            "instances": len(w.texts),
                            "add_one_instance_us_median": float(np.median(join_us)) if join_us else None,
