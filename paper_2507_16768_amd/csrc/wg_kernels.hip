@@ -786,6 +786,18 @@ class_scan_batch_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
         auto drain = [&]() {
             const uint32_t nq = n_que;
             __syncthreads();                         // every thread has read the length
+            // what a round needs of its tokens is requested a round ahead, so that the trip to
+            // memory of one round runs under the work of the round before
+            uint32_t q_next = 0, L_next = 0;
+            uint64_t d_next = 0;
+            auto request = [&](uint32_t i0) {
+                const bool act = i0 + tid < nq;
+                q_next = que[act ? i0 + tid : 0u];
+                const uint32_t tok = g * kScanGroup + (q_next & (kScanGroup - 1u));   // below V
+                L_next = act ? Vc.len8[tok] : 0u;
+                d_next = Vc.chunks[tok];
+            };
+            if (nq) request(0u);
             for (uint32_t i0 = 0; i0 < nq; i0 += kScanThreads) {
                 if (long_bound + kScanThreads > kScanLong) {
                     // the second queue may be short of room for a round: count exactly, empty it if need be
@@ -797,13 +809,12 @@ class_scan_batch_kernel(DeviceTable T, DeviceVocab Vc, DeviceCache Cc)
                 }
                 long_bound += kScanThreads;
                 stage_room();                        // (after the second stage may have run: it stages entries too)
+                const uint32_t q = q_next, Lq = L_next;
+                const uint64_t d0 = d_next;
+                if (i0 + kScanThreads < nq) request(i0 + kScanThreads);
                 if (i0 + wave * 64u >= nq) continue;                    // nothing for this wavefront in the last round
-                const bool act = i0 + tid < nq;
-                const uint32_t q = que[act ? i0 + tid : 0u];
                 const uint32_t t = q >> 11, idx = q & (kScanGroup - 1u);
-                const uint32_t tok = g * kScanGroup + idx;               // below V
-                const uint32_t Lq = act ? Vc.len8[tok] : 0u;
-                const uint64_t d0 = Vc.chunks[tok];
+                const uint32_t tok = g * kScanGroup + idx;
                 uint32_t res = 0, j = 0;
                 const bool decided = Lq == 0u || scan_chunk(lut[t], d0, Lq, 0, res, j);
                 // undecided: to the second queue
