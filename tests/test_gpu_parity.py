@@ -351,6 +351,7 @@ def test_random_trees_every_state_every_token(torch_cuda, restart):
         texts = [ws.to_text(t) for t in trees]
         o = O.Oracle(texts, None, ov, restart=restart)
         h = wg.Handle(texts, None, gv, flags=wg.EOS_RESTART if restart else wg.EOS_STOP)
+        h.set_scan_batch((0, 8, 3)[case % 3])              # the class scan table by table, and several at a time
         st = _all_states(o)
         n_states += len(st)
         h.reserve_batch(len(st))
