@@ -365,6 +365,7 @@ __device__ __forceinline__ void stage_entry(uint2 *ent, uint32_t *n_ent, bool ea
 }
 
 constexpr uint32_t kScanThreads = 256;
+constexpr uint32_t kScanWgs = 5;          // workgroups of class_scan a compute unit holds (its registers)
 constexpr uint32_t kScanPer = kScanGroup / kScanThreads;     // tokens per lane of class_scan
 static_assert(kScanPer * kScanThreads == kScanGroup, "a lane owns a whole number of tokens");
 
@@ -1701,9 +1702,11 @@ hipError_t launch_fill(const DeviceTable &T, const DeviceVocab &Vc, const Device
     else launch(lookup_kernel, dim3(cdiv(B, 64)), dim3(64), 0, s, ev, T, Cc, static_cast<const wg_state_t *>(states), B);
     // the number of misses is only known on the device: both build kernels stride a fixed
     // grid over whatever the lookup queued and fall through when nothing is queued
+    // (a call scans at most one class table per request, and no more than the handle has; the
+    // kernels hold 5 workgroups per compute unit, and a launch of more costs a warm step time)
     uint32_t groups = cdiv(Vc.V, kScanGroup);
-    uint64_t scan_items = (uint64_t)B * groups;
-    uint32_t cap = n_cu * 8u;
+    uint64_t scan_items = (uint64_t)(B < T.n_classes ? B : T.n_classes) * groups;
+    uint32_t cap = n_cu * kScanWgs;
     // a handle with few class tables scans them one per work item; with many, a call may bring so
     // many that they are taken several at a time
     if (Cc.scan_batch ? Cc.scan_batch > 1u : (uint64_t)T.n_classes * groups > kScanBatchFrom)
