@@ -68,6 +68,16 @@ typedef enum { WG_F32 = 0, WG_BF16 = 1 } wg_dtype_t;
  * further EOS), or re-arm the request at its template's start state (continuous
  * batching: the slot is reused by the next request of the same shape). */
 enum { WG_EOS_STOP = 0u, WG_EOS_RESTART = 1u };
+/* May be or-ed to either: states with equal futures share their cache keys, also across
+ * instances of different shapes and inside one instance.  Two states are taken as equal when
+ * they agree in what they do with every byte (kind, literal byte, allow / wait sets, bound,
+ * whether EOS is accepted) and, one level less deep, so do their successors, down to as many
+ * levels as the longest token has bytes: no token can tell such states apart, so their masks are
+ * the same (the global cache of the section "Mask Generation and Global Caching": a mask depends
+ * on what the operators ahead accept, not on which request or template they belong to).  Costs
+ * host time when instances are compiled or added (every new state is compared level by level);
+ * without it only instances that are equal as a whole share keys. */
+enum { WG_SHARE_STATES = 2u };
 
 typedef enum {
     WG_OK = 0,
@@ -112,6 +122,7 @@ typedef struct {
     uint32_t max;           /* WAIT: bound on consumed allow-bytes, or WG_UNBOUNDED */
     uint32_t tmpl;          /* template instance the state belongs to */
     uint32_t n_keys;        /* distinct masks this state can have (budget variants) */
+    uint32_t key;           /* the first of its cache keys (states that share keys report the same) */
 } wg_state_info_t;
 
 /* ---- vocabulary (the token map the structure factory of the section "Collaborative Parsing"
@@ -140,7 +151,8 @@ void wg_vocab_destroy(wg_vocab_t v);
  * heterogeneous batch: state ids are global to the handle.  Every instance has state ids of
  * its own; instances whose states are equal one for one (the same structure instantiated with
  * the same arguments) share their cache keys, so their masks are built and held once (the global
- * cache of the section "Mask Generation and Global Caching").
+ * cache of the section "Mask Generation and Global Caching"); with WG_SHARE_STATES in flags so do
+ * any two states that no token can tell apart.
  * wg_lower does the host part only (no GPU needed) and returns an inspectable table;
  * lmax is the longest token length the masks will be built for. */
 int wg_lower(const char *const *templates, const wg_args_t *args, uint32_t n_templates,

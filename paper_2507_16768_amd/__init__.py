@@ -6,5 +6,5 @@ device-resident cache, logit masking, state advance) behind a small C ABI.
 from .binding import (  # noqa: F401
     WgError, Vocab, Handle, Table, apply_mask, masked_argmax, masked_topk, masked_topk_workspace, masked_topk_static, masked_topk_static_capacity, select_tokens, regex_to_template, marshal_templates,
     load_library, library_path,
-    F32, BF16, EOS_STOP, EOS_RESTART, SID_FINAL, SID_ERROR,
+    F32, BF16, EOS_STOP, EOS_RESTART, SHARE_STATES, SID_FINAL, SID_ERROR,
 )

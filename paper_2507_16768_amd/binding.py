@@ -16,6 +16,7 @@ from . import build as _build
 
 F32, BF16 = 0, 1
 EOS_STOP, EOS_RESTART = 0, 1
+SHARE_STATES = 2          # or-ed to either: states with equal futures share their cache keys
 SID_FINAL, SID_ERROR = 0, 0xFFFFFFFF
 
 _lib = None
@@ -40,7 +41,7 @@ class _Stats(C.Structure):
 
 class _StateInfo(C.Structure):
     _fields_ = [(k, C.c_uint32) for k in ("kind", "byte", "next_a", "next_b", "eos_next", "max",
-                                           "tmpl", "n_keys")]
+                                           "tmpl", "n_keys", "key")]
 
 
 class _Profile(C.Structure):

@@ -312,7 +312,7 @@ int wg_lower(const char *const *templates, const wg_args_t *args, uint32_t n_tem
     if (!out) return fail(WG_ERR_INVALID, "wg_lower: out is null");
     *out = nullptr;
     if (!templates || n_templates == 0) return fail(WG_ERR_INVALID, "wg_lower: no templates");
-    if (flags & ~(uint32_t)WG_EOS_RESTART) return fail(WG_ERR_INVALID, "wg_lower: unknown flag bits");
+    if (flags & ~(uint32_t)(WG_EOS_RESTART | WG_SHARE_STATES)) return fail(WG_ERR_INVALID, "wg_lower: unknown flag bits");
     try {
         std::unique_ptr<wg_table_s> t(new wg_table_s(flags, lmax));
         t->low.add(templates, args, n_templates);
@@ -370,7 +370,7 @@ int wg_table_state(wg_table_t t, uint32_t sid, wg_state_info_t *out) {
     const StateDesc &d = tb.states[sid];
     out->kind = d.kind_byte & 0xFFu; out->byte = (d.kind_byte >> 8) & 0xFFu;
     out->next_a = d.next_a; out->next_b = d.next_b; out->eos_next = d.eos_next; out->max = d.max;
-    out->tmpl = tb.tmpl[sid]; out->n_keys = tb.key_count[sid];
+    out->tmpl = tb.tmpl[sid]; out->n_keys = tb.key_count[sid]; out->key = d.key_base;
     return WG_OK;
 }
 
@@ -408,7 +408,7 @@ int wg_compile(const char *const *templates, const wg_args_t *args, uint32_t n_t
     *out = nullptr;
     if (!vocab) return fail(WG_ERR_INVALID, "wg_compile: vocab is null");
     if (!templates || n_templates == 0) return fail(WG_ERR_INVALID, "wg_compile: no templates");
-    if (flags & ~(uint32_t)WG_EOS_RESTART) return fail(WG_ERR_INVALID, "wg_compile: unknown flag bits");
+    if (flags & ~(uint32_t)(WG_EOS_RESTART | WG_SHARE_STATES)) return fail(WG_ERR_INVALID, "wg_compile: unknown flag bits");
     std::unique_ptr<wg_handle_s, void (*)(wg_handle_t)> h(
         new (std::nothrow) wg_handle_s(flags, vocab->dv.lmax), wg_destroy);
     if (!h) return fail(WG_ERR_NOMEM, "wg_compile: out of host memory");

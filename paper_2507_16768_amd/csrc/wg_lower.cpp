@@ -414,6 +414,23 @@ struct LoweringState {
     // instance of the same shape -- the same structure instantiated with the same arguments --
     // has, state for state, the same masks, so its states share that instance's cache keys.
     std::unordered_map<std::string, uint32_t> shapes;
+    // WG_SHARE_STATES: states by what they and the states ahead of them do with bytes.  `own_part`
+    // numbers the tuples {kind and literal byte, class table, bound, EOS accepted} in the order
+    // they are first seen, `levels` the tuples {level, the state's own part, the numbers of its
+    // two successors one level lower}.  A state's number at level lmax - 1 (its own part when
+    // lmax is 1) stands for everything a token can see of it; `sig_key` has the first cache key
+    // of the first state seen with each such number.
+    struct TupleHash {
+        size_t operator()(const std::array<uint32_t, 4> &a) const {
+            uint64_t h = (uint64_t)a[0] * 0x9E3779B97F4A7C15ull;
+            h = (h ^ a[1]) * 0xC2B2AE3D27D4EB4Full;
+            h = (h ^ a[2]) * 0x165667B19E3779F9ull;
+            h = (h ^ a[3]) * 0x9E3779B97F4A7C15ull;
+            return (size_t)(h ^ (h >> 32));
+        }
+    };
+    std::unordered_map<std::array<uint32_t, 4>, uint32_t, TupleHash> own_part, levels;
+    std::unordered_map<uint32_t, uint32_t> sig_key;
 };
 
 namespace {
@@ -501,6 +518,7 @@ void Lowering::add(const char *const *templates, const wg_args_t *args, uint32_t
     t.key_count.resize(t.states.size());
     uint32_t k = n_keys0;
     std::vector<std::string> new_shapes;                              // to take back if memory runs out half way
+    std::vector<uint32_t> new_sigs;
     try {
         for (const auto &span : spans) {
             const uint32_t first = span.first, end = span.second;
@@ -518,13 +536,55 @@ void Lowering::add(const char *const *templates, const wg_args_t *args, uint32_t
             }
             new_shapes.push_back(shape);
             st_->shapes.emplace(std::move(shape), first);
+            auto inside = [&](uint32_t sid) { return sid == WG_SID_ERROR || sid == WG_SID_FINAL || (sid >= first && sid <= end); };
+            bool closed = true;                      // (every successor lies in the instance itself)
+            for (uint32_t s = first; s <= end; s++) closed = closed && inside(t.states[s].next_a) && inside(t.states[s].next_b);
+            if (!(t.flags & WG_SHARE_STATES) || !closed) {
+                for (uint32_t s = first; s <= end; s++) {
+                    t.states[s].key_base = k;
+                    k += t.key_count[s];
+                }
+                continue;
+            }
+            // States with equal futures share their keys.  Level 0 numbers a state by its own
+            // part: kind and literal byte, class table, bound, whether EOS is accepted (where
+            // EOS leads does not show in a mask).  Level l + 1 adds the level-l numbers of the
+            // two successors, which lie in the same instance or are FINAL / none.  A token of n
+            // bytes sees the states up to n - 1 transitions ahead, so lmax - 1 levels decide.
+            const uint32_t n_inst = end - first + 1u;
+            std::vector<uint32_t> own(n_inst), cur(n_inst), nxt(n_inst);
+            auto number = [](auto &map, const std::array<uint32_t, 4> &tuple) {
+                return map.emplace(tuple, (uint32_t)map.size()).first->second;
+            };
+            auto at_level = [&](const std::vector<uint32_t> &ids, uint32_t sid) {
+                return sid == WG_SID_ERROR ? 0xFFFFFFFFu : sid == WG_SID_FINAL ? 0xFFFFFFFEu : ids[sid - first];
+            };
             for (uint32_t s = first; s <= end; s++) {
+                const StateDesc &d = t.states[s];
+                const uint32_t kind = d.kind_byte & 0xFFu;
+                const bool ckpt = kind == WG_KIND_WAIT || kind == WG_KIND_COND;
+                own[s - first] = cur[s - first] =
+                    number(st_->own_part, {d.kind_byte, ckpt ? d.cls : 0u, d.max, d.eos_next != WG_SID_ERROR ? 1u : 0u});
+            }
+            for (uint32_t level = 1; level < t.lmax; level++) {
+                for (uint32_t s = first; s <= end; s++) {
+                    const StateDesc &d = t.states[s];
+                    nxt[s - first] = number(st_->levels, {level, own[s - first], at_level(cur, d.next_a), at_level(cur, d.next_b)});
+                }
+                cur.swap(nxt);
+            }
+            for (uint32_t s = first; s <= end; s++) {
+                const auto known = st_->sig_key.find(cur[s - first]);
+                if (known != st_->sig_key.end()) { t.states[s].key_base = known->second; continue; }
+                st_->sig_key.emplace(cur[s - first], k);
+                new_sigs.push_back(cur[s - first]);
                 t.states[s].key_base = k;
                 k += t.key_count[s];
             }
         }
     } catch (...) {
         for (const std::string &sh : new_shapes) st_->shapes.erase(sh);
+        for (uint32_t sig : new_sigs) st_->sig_key.erase(sig);
         roll_back();
         throw;
     }

@@ -18,10 +18,10 @@ def start_states(o, w):
     return np.array([[o.start_state(int(t)), 0] for t in w.request_template], dtype=np.uint32)
 
 
-def make_gpu(w, restart=True):
+def make_gpu(w, restart=True, share=False):
     import paper_2507_16768_amd as wg
     v = wg.Vocab(w.vocab.bytes, w.vocab.offsets, w.vocab.eos_id)
-    h = wg.Handle(w.texts, w.args, v, flags=wg.EOS_RESTART if restart else wg.EOS_STOP)
+    h = wg.Handle(w.texts, w.args, v, flags=(wg.EOS_RESTART if restart else wg.EOS_STOP) | (wg.SHARE_STATES if share else 0))
     return v, h
 
 

@@ -23,12 +23,12 @@ def torch_cuda():
     return torch
 
 
-def _replay(torch, w, steps, check_logits_every=1, label="", fused=False):
+def _replay(torch, w, steps, check_logits_every=1, label="", fused=False, share=False):
     """Oracle generates the trajectory; the GPU replays it step by step (with fused=True through
     wg_advance_fill_masks instead of wg_advance + wg_fill_masks)."""
     import paper_2507_16768_amd as wg
     o = H.make_oracle(w)
-    v, h = H.make_gpu(w)
+    v, h = H.make_gpu(w, share=share)
     st0 = H.start_states(o, w)
     assert (h.start_states[w.request_template] == st0).all()
     V, W, B = w.vocab.V, (w.vocab.V + 31) // 32, w.B
@@ -109,6 +109,20 @@ def test_reduced_configs_every_step(torch_cuda, idx, V, B, steps):
     h, o, nkeys = _replay(torch_cuda, w, steps, label="cfg%d-small" % idx)
     s = h.cache_stats()
     assert s["lookups"] == B * steps and s["builds"] == nkeys and 0 < s["hits"] <= B * steps - nkeys
+
+
+@pytest.mark.parametrize("idx,V,B,steps", [(2, 5003, 7, 64), (3, 4099, 9, 64), (4, 6001, 10, 64), (5, 7013, 33, 48)])
+def test_reduced_configs_with_states_of_equal_futures_sharing_keys(torch_cuda, idx, V, B, steps):
+    """WG_SHARE_STATES: every mask, masked logit and state as without it; no more rows built than
+    there are distinct (state, budget) pairs, and fewer keys in the handle than states ask for."""
+    w = ws.make_workload(idx, V=V, B=B, steps=steps)
+    h, o, nkeys = _replay(torch_cuda, w, steps, check_logits_every=8, label="cfg%d-shared" % idx, share=True)
+    s = h.cache_stats()
+    assert s["lookups"] == B * steps and 0 < s["builds"] <= nkeys
+    v2, plain = H.make_gpu(w)
+    assert s["keys"] <= plain.cache_stats()["keys"]
+    if idx == 5:
+        assert s["keys"] < plain.cache_stats()["keys"]
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])

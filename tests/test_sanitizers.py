@@ -56,16 +56,20 @@ def _case_file(path):
         n = len(w.texts)
         case(w.texts, w.args, 1, 24)
         case(w.texts, w.args, 0, 8, chunks=[[i] for i in range(n)])       # one add per instance
+        case(w.texts, w.args, 3, 24 if idx != 4 else 6, chunks=[[i] for i in range(n)])   # states of equal futures share keys
     rng = Counter(5, 2)
     for _ in range(60):
         trees = [TreeGen(rng, alphabet=b"ab<.", max_depth=3, write_len=(0, 3), big=False).tree(1, 20)
                  for _ in range(rng.between(1, 3))]
-        case([ws.to_text(t) for t in trees], None, rng.between(0, 1), 8)
+        case([ws.to_text(t) for t in trees], None, rng.between(0, 3), 8)
     bad = ["Sequence(Write(\"a\")", "Frobnicate()", "Wait(allow={a})", "Write($missing)", "Wait(allow={a, <eos>}, wait={b})",
            "Sequence(Wait(allow={a}, wait={<eos>}), Write(\"b\"))", "Wait(allow={[z-a]}, wait={b})", "Write(\"\\x4\")",
            "IfElse(condition=Wait(allow={a}, true_waits={x}, false_waits={x}), if_body=None, else_body=None)", "", "(",
            "Wait(allow={a}, wait={b}, max=99999999999)", "Sequence(" * 40]
     good = "Sequence(Write(\"ab\"), Wait(allow={a}, wait={b}, max=3))"
+    lines.append("C 3 8")
+    for b in bad[:4]:                                        # the same with shared keys: what a failed add numbered is taken back
+        lines += ["T " + _hex(good), "G", "T " + _hex(good), "T " + _hex(b), "G"]
     lines.append("C 1 8")
     for b in bad:                                            # a failing add between good ones
         lines += ["T " + _hex(good), "G", "T " + _hex(good), "T " + _hex(b), "G"]
