@@ -420,16 +420,40 @@ struct LoweringState {
     // two successors one level lower}.  A state's number at level lmax - 1 (its own part when
     // lmax is 1) stands for everything a token can see of it; `sig_key` has the first cache key
     // of the first state seen with each such number.
-    struct TupleHash {
-        size_t operator()(const std::array<uint32_t, 4> &a) const {
-            uint64_t h = (uint64_t)a[0] * 0x9E3779B97F4A7C15ull;
-            h = (h ^ a[1]) * 0xC2B2AE3D27D4EB4Full;
-            h = (h ^ a[2]) * 0x165667B19E3779F9ull;
-            h = (h ^ a[3]) * 0x9E3779B97F4A7C15ull;
-            return (size_t)(h ^ (h >> 32));
+    // (an open-addressing table: a tuple's number is its place in `tuples`; the lowering of a
+    // workload numbers a million tuples, which a node per tuple makes ten times slower)
+    struct Numbering {
+        std::vector<std::array<uint32_t, 4>> tuples;
+        std::vector<uint32_t> slots;                  // number + 1, 0: free; a power of two of them
+        static uint64_t mix(const std::array<uint32_t, 4> &a) {
+            uint64_t h = ((uint64_t)a[0] << 32 | a[1]) * 0x9E3779B97F4A7C15ull;
+            h ^= h >> 29;
+            h += ((uint64_t)a[2] << 32 | a[3]) * 0xC2B2AE3D27D4EB4Full;
+            h ^= h >> 31;
+            return h * 0x165667B19E3779F9ull;
+        }
+        void grow() {
+            std::vector<uint32_t> wider(slots.empty() ? 1024u : slots.size() * 2u, 0u);
+            for (uint32_t i = 0; i < tuples.size(); i++) {
+                size_t at = (mix(tuples[i]) >> 20) & (wider.size() - 1u);
+                while (wider[at]) at = (at + 1u) & (wider.size() - 1u);
+                wider[at] = i + 1u;
+            }
+            slots.swap(wider);
+        }
+        uint32_t number(const std::array<uint32_t, 4> &t) {
+            if ((tuples.size() + 1u) * 2u > slots.size()) grow();
+            size_t at = (mix(t) >> 20) & (slots.size() - 1u);
+            while (slots[at]) {
+                if (tuples[slots[at] - 1u] == t) return slots[at] - 1u;
+                at = (at + 1u) & (slots.size() - 1u);
+            }
+            tuples.push_back(t);
+            slots[at] = (uint32_t)tuples.size();
+            return (uint32_t)tuples.size() - 1u;
         }
     };
-    std::unordered_map<std::array<uint32_t, 4>, uint32_t, TupleHash> own_part, levels;
+    Numbering own_part, levels;
     std::unordered_map<uint32_t, uint32_t> sig_key;
 };
 
@@ -553,9 +577,6 @@ void Lowering::add(const char *const *templates, const wg_args_t *args, uint32_t
             // bytes sees the states up to n - 1 transitions ahead, so lmax - 1 levels decide.
             const uint32_t n_inst = end - first + 1u;
             std::vector<uint32_t> own(n_inst), cur(n_inst), nxt(n_inst);
-            auto number = [](auto &map, const std::array<uint32_t, 4> &tuple) {
-                return map.emplace(tuple, (uint32_t)map.size()).first->second;
-            };
             auto at_level = [&](const std::vector<uint32_t> &ids, uint32_t sid) {
                 return sid == WG_SID_ERROR ? 0xFFFFFFFFu : sid == WG_SID_FINAL ? 0xFFFFFFFEu : ids[sid - first];
             };
@@ -564,12 +585,12 @@ void Lowering::add(const char *const *templates, const wg_args_t *args, uint32_t
                 const uint32_t kind = d.kind_byte & 0xFFu;
                 const bool ckpt = kind == WG_KIND_WAIT || kind == WG_KIND_COND;
                 own[s - first] = cur[s - first] =
-                    number(st_->own_part, {d.kind_byte, ckpt ? d.cls : 0u, d.max, d.eos_next != WG_SID_ERROR ? 1u : 0u});
+                    st_->own_part.number({d.kind_byte, ckpt ? d.cls : 0u, d.max, d.eos_next != WG_SID_ERROR ? 1u : 0u});
             }
             for (uint32_t level = 1; level < t.lmax; level++) {
                 for (uint32_t s = first; s <= end; s++) {
                     const StateDesc &d = t.states[s];
-                    nxt[s - first] = number(st_->levels, {level, own[s - first], at_level(cur, d.next_a), at_level(cur, d.next_b)});
+                    nxt[s - first] = st_->levels.number({level, own[s - first], at_level(cur, d.next_a), at_level(cur, d.next_b)});
                 }
                 cur.swap(nxt);
             }
