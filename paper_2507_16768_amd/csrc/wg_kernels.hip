@@ -5,6 +5,8 @@
 //   class_scan   : every vocabulary token against one checkpoint's byte-class table: a first look
 //                  that settles most tokens with one instruction or table look-up each (64-lane
 //                  ballots pack the row words), the rest byte by byte through the table in LDS
+//                  (class_scan_batch, for handles with many tables: several tables per pass
+//                  over the tokens, the first look from the vocabulary's rows by byte value)
 //   key_build    : a workgroup assembles the row of a missing key (or its words for one token
 //                  range) in LDS from the class index and the tokens that leave the state early,
 //                  which it finds in the vocabulary's indexes (byte order, byte pairs) or in the
